@@ -165,7 +165,7 @@ const char* ah_last_error(void);
  * roofline measurement.  All pointers are device pointers; shapes must obey
  * the tile constraints stated with each (else AH_EUNSUPPORTED). */
 
-/* C[M,N] (bf16) = A[M,K] B[K,N] + bias[N] (bias may be NULL).  M, N multiples of 128, K of 64. */
+/* C[M,N] (bf16) = A[M,K] B[K,N] + bias[N] (bias may be NULL).  M, N and K multiples of 128. */
 int ah_gemm_nn(const void* A, const void* B, const void* bias, void* C, int M, int N, int K, void* hip_stream);
 /* C[M,N] (bf16) = A[M,K] B[N,K]^T.  Same constraints. */
 int ah_gemm_nt(const void* A, const void* B, void* C, int M, int N, int K, void* hip_stream);

@@ -1,0 +1,196 @@
+"""ctypes binding of include/ah_stage.h: argument marshalling only.
+
+Device memory and streams come from PyTorch (ROCm); tensors are passed as raw
+device pointers.  The library must have been built (paper_2512_20953_amd/build.py
+or __graft_entry__.build()); a missing library is an ImportError-level failure,
+there is no fallback path.
+"""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+AH_ARCH_GPT, AH_ARCH_LLAMA = 0, 1
+PARAM_INDEX = {"ln1_g": 0, "ln1_b": 1, "wqkv": 2, "bqkv": 3, "wo": 4, "bo": 5,
+               "ln2_g": 6, "ln2_b": 7, "w1": 8, "b1": 9, "w2": 10, "b2": 11}
+# names the layer's tensors go by elsewhere (LLaMA: fused gate|up and down)
+PARAM_ALIASES = {"wgu": "w1", "wd": "w2"}
+
+
+class AhError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__("ah status %d: %s" % (status, msg))
+        self.status = status
+
+
+class StageConfig(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("arch", C.c_int32), ("n_layers", C.c_int32), ("hidden", C.c_int32),
+                ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn_hidden", C.c_int32), ("tp_degree", C.c_int32),
+                ("tp_rank", C.c_int32), ("seq_len", C.c_int32), ("microbatch_size", C.c_int32),
+                ("n_microbatches", C.c_int32), ("max_in_flight", C.c_int32), ("recompute", C.c_int32),
+                ("norm_eps", C.c_float), ("rope_base", C.c_float)]
+
+    @classmethod
+    def make(cls, arch="gpt", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=1024, tp=1, tp_rank=0, seq=128, mb=1,
+             n_mb=1, max_in_flight=1, recompute=0, norm_eps=0.0, rope_base=0.0):
+        return cls(C.sizeof(cls), AH_ARCH_LLAMA if arch == "llama" else AH_ARCH_GPT, n_layers, hidden, n_heads, head_dim,
+                   ffn, tp, tp_rank, seq, mb, n_mb, max_in_flight, recompute, norm_eps, rope_base)
+
+
+class _Sizes(C.Structure):
+    _fields_ = [("param_elems", C.c_uint64), ("param_bytes", C.c_uint64), ("grad_bytes", C.c_uint64),
+                ("activation_bytes_per_slot", C.c_uint64), ("activation_bytes_per_layer_per_slot", C.c_uint64),
+                ("workspace_bytes", C.c_uint64)]
+
+
+class _Buffers(C.Structure):
+    _fields_ = [("params", C.c_void_p), ("grads", C.c_void_p), ("activations", C.c_void_p), ("workspace", C.c_void_p)]
+
+
+class _Profile(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_layers", C.c_int32), ("fwd_ms", C.POINTER(C.c_float)),
+                ("bwd_ms", C.POINTER(C.c_float)), ("stage_fwd_ms", C.c_float), ("stage_bwd_ms", C.c_float),
+                ("iteration_ms", C.c_float), ("peak_activation_bytes", C.c_uint64),
+                ("activation_bytes_per_layer_per_slot", C.c_uint64), ("param_bytes", C.c_uint64), ("grad_bytes", C.c_uint64)]
+
+
+def library_path():
+    return os.path.join(HERE, "libahstage.so")
+
+
+def _load():
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError("libahstage.so is not built: run `python -m paper_2512_20953_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback implementation")
+    L = C.CDLL(path)
+    L.ah_last_error.restype = C.c_char_p
+    vp, i = C.c_void_p, C.c_int
+    L.ah_stage_query_sizes.argtypes = [C.POINTER(StageConfig), C.POINTER(_Sizes)]
+    L.ah_stage_create.argtypes = [C.POINTER(StageConfig), C.POINTER(_Buffers), C.POINTER(vp)]
+    L.ah_stage_destroy.argtypes = [vp]
+    L.ah_stage_param_layout.argtypes = [vp, i, i, C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    L.ah_stage_forward.argtypes = [vp, i, vp, vp, vp]
+    L.ah_stage_backward.argtypes = [vp, i, vp, vp, vp]
+    L.ah_stage_grads.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_uint64)]
+    L.ah_stage_zero_grads.argtypes = [vp, vp]
+    L.ah_stage_profile.argtypes = [vp, i, i, C.POINTER(_Profile)]
+    L.ah_gemm_nn.argtypes = [vp, vp, vp, vp, i, i, i, vp]
+    L.ah_gemm_nt.argtypes = [vp, vp, vp, i, i, i, vp]
+    L.ah_gemm_tn.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    L.ah_attention_fwd.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    L.ah_attention_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+    return L
+
+
+lib = _load()
+
+
+def _check(rc):
+    if rc != 0:
+        raise AhError(rc, lib.ah_last_error().decode())
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def query_sizes(cfg):
+    s = _Sizes()
+    _check(lib.ah_stage_query_sizes(C.byref(cfg), C.byref(s)))
+    return {k: int(getattr(s, k)) for k, _ in _Sizes._fields_}
+
+
+class Stage:
+    """A stage over torch-allocated device buffers."""
+
+    def __init__(self, cfg, device="cuda:0"):
+        import torch
+        self.cfg = cfg
+        self.sizes = query_sizes(cfg)
+        self.device = torch.device(device)
+        self.params = torch.zeros(self.sizes["param_elems"], dtype=torch.bfloat16, device=self.device)
+        self.grads = torch.zeros(self.sizes["param_elems"], dtype=torch.float32, device=self.device)
+        self.activations = torch.empty(self.sizes["activation_bytes_per_slot"] * cfg.max_in_flight, dtype=torch.uint8,
+                                       device=self.device)
+        self.workspace = torch.empty(self.sizes["workspace_bytes"], dtype=torch.uint8, device=self.device)
+        bufs = _Buffers(self.params.data_ptr(), self.grads.data_ptr(), self.activations.data_ptr(), self.workspace.data_ptr())
+        h = C.c_void_p()
+        _check(lib.ah_stage_create(C.byref(cfg), C.byref(bufs), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib.ah_stage_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def param_layout(self, layer, name):
+        which = PARAM_INDEX[PARAM_ALIASES.get(name, name)]
+        off, r, c = C.c_uint64(), C.c_int32(), C.c_int32()
+        _check(lib.ah_stage_param_layout(self._h, layer, which, C.byref(off), C.byref(r), C.byref(c)))
+        return off.value, r.value, c.value
+
+    def param_view(self, layer, name):
+        off, r, c = self.param_layout(layer, name)
+        v = self.params[off:off + r * c]
+        return v.view(r, c) if r > 1 else v
+
+    def grad_view(self, layer, name):
+        off, r, c = self.param_layout(layer, name)
+        v = self.grads[off:off + r * c]
+        return v.view(r, c) if r > 1 else v
+
+    def forward(self, slot, x, y, stream=None):
+        _check(lib.ah_stage_forward(self._h, slot, _ptr(x), _ptr(y), _stream(stream)))
+
+    def backward(self, slot, dy, dx, stream=None):
+        _check(lib.ah_stage_backward(self._h, slot, _ptr(dy), _ptr(dx), _stream(stream)))
+
+    def zero_grads(self, stream=None):
+        _check(lib.ah_stage_zero_grads(self._h, _stream(stream)))
+
+    def grads_ptr(self):
+        p, n = C.c_void_p(), C.c_uint64()
+        _check(lib.ah_stage_grads(self._h, C.byref(p), C.byref(n)))
+        return p.value, n.value
+
+    def profile(self, warmup=2, iters=5):
+        L = self.cfg.n_layers
+        f, b = (C.c_float * L)(), (C.c_float * L)()
+        p = _Profile(C.sizeof(_Profile), L, f, b)
+        _check(lib.ah_stage_profile(self._h, warmup, iters, C.byref(p)))
+        return {"fwd_ms": list(f), "bwd_ms": list(b), "stage_fwd_ms": p.stage_fwd_ms, "stage_bwd_ms": p.stage_bwd_ms,
+                "iteration_ms": p.iteration_ms, "peak_activation_bytes": int(p.peak_activation_bytes),
+                "activation_bytes_per_layer_per_slot": int(p.activation_bytes_per_layer_per_slot),
+                "param_bytes": int(p.param_bytes), "grad_bytes": int(p.grad_bytes)}
+
+
+def gemm_nn(A, B, bias, Cout, stream=None):
+    M, K = A.shape
+    _check(lib.ah_gemm_nn(_ptr(A), _ptr(B), _ptr(bias), _ptr(Cout), M, B.shape[1], K, _stream(stream)))
+
+
+def gemm_nt(A, B, Cout, stream=None):
+    M, K = A.shape
+    _check(lib.ah_gemm_nt(_ptr(A), _ptr(B), _ptr(Cout), M, B.shape[0], K, _stream(stream)))
+
+
+def gemm_tn(A, B, Cout, beta, stream=None):
+    K, M = A.shape
+    _check(lib.ah_gemm_tn(_ptr(A), _ptr(B), _ptr(Cout), M, B.shape[1], K, int(beta), _stream(stream)))
+
+
+def attention_fwd(qkv, o, lse, B, S, nh, d, stream=None):
+    _check(lib.ah_attention_fwd(_ptr(qkv), _ptr(o), _ptr(lse), B, S, nh, d, _stream(stream)))
+
+
+def attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, stream=None):
+    _check(lib.ah_attention_bwd(_ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(delta), B, S, nh, d, _stream(stream)))

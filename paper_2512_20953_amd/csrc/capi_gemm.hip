@@ -1,0 +1,36 @@
+// C ABI: single-GEMM entry points (declared in include/ah_stage.h).
+#include "ah_stage.h"
+#include "capi_util.h"
+#include "kernels.h"
+
+using namespace ah;
+
+static const char* kShapeMsg = "M, N, K must be positive multiples of 128";
+
+extern "C" int ah_gemm_nn(const void* A, const void* B, const void* bias, void* C, int M, int N, int K, void* stream) {
+  if (!A || !B || !C) return set_error(AH_EINVAL, "ah_gemm_nn: NULL pointer");
+  if (!gemm_shape_ok(M, N, K)) return set_error(AH_EUNSUPPORTED, "ah_gemm_nn: %s", kShapeMsg);
+  GemmArgs g = {};
+  g.A = A; g.B = B; g.C = C; g.bias = bias;
+  g.lda = K; g.ldb = N; g.ldc = N; g.M = M; g.N = N; g.K = K;
+  return hip_status(launch_gemm(GEMM_NN, EPI_BF16, g, (hipStream_t)stream), "ah_gemm_nn");
+}
+
+extern "C" int ah_gemm_nt(const void* A, const void* B, void* C, int M, int N, int K, void* stream) {
+  if (!A || !B || !C) return set_error(AH_EINVAL, "ah_gemm_nt: NULL pointer");
+  if (!gemm_shape_ok(M, N, K)) return set_error(AH_EUNSUPPORTED, "ah_gemm_nt: %s", kShapeMsg);
+  GemmArgs g = {};
+  g.A = A; g.B = B; g.C = C;
+  g.lda = K; g.ldb = K; g.ldc = N; g.M = M; g.N = N; g.K = K;
+  return hip_status(launch_gemm(GEMM_NT, EPI_BF16, g, (hipStream_t)stream), "ah_gemm_nt");
+}
+
+extern "C" int ah_gemm_tn(const void* A, const void* B, float* C, int M, int N, int K, int beta, void* stream) {
+  if (!A || !B || !C) return set_error(AH_EINVAL, "ah_gemm_tn: NULL pointer");
+  if (beta != 0 && beta != 1) return set_error(AH_EINVAL, "ah_gemm_tn: beta must be 0 or 1");
+  if (!gemm_shape_ok(M, N, K)) return set_error(AH_EUNSUPPORTED, "ah_gemm_tn: %s", kShapeMsg);
+  GemmArgs g = {};
+  g.A = A; g.B = B; g.C = C;
+  g.lda = M; g.ldb = N; g.ldc = N; g.M = M; g.N = N; g.K = K; g.beta = beta;
+  return hip_status(launch_gemm(GEMM_TN, EPI_F32_ACC, g, (hipStream_t)stream), "ah_gemm_tn");
+}

@@ -1,0 +1,58 @@
+// Internal launch interface between the stage orchestration and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ah {
+
+enum GemmLayout { GEMM_NN = 0, GEMM_NT = 1, GEMM_TN = 2 };
+enum GemmEpilogue {
+  EPI_BF16 = 0,      // C = acc (+ bias[n])
+  EPI_GELU = 1,      // C = u = acc + bias[n];  C2 = gelu(u)
+  EPI_RESID = 2,     // C = acc (+ bias[n]) + aux[m, n]
+  EPI_GELU_BWD = 3,  // C = acc * gelu'(aux[m, n])
+  EPI_F32_ACC = 4    // C (fp32) = beta * C + acc
+};
+
+struct GemmArgs {
+  const void* A;     // NN/NT: [M, K] row-major;  TN: [K, M] row-major
+  const void* B;     // NN/TN: [K, N] row-major;  NT: [N, K] row-major
+  void* C;           // [M, N]
+  void* C2;          // EPI_GELU second output
+  const void* bias;  // [N] bf16 or NULL
+  const void* aux;   // [M, N] bf16 (residual, or the pre-activation for EPI_GELU_BWD)
+  int lda, ldb, ldc, ld_aux;
+  int M, N, K;
+  int beta;
+};
+
+// M, N, K multiples of 128, all leading dimensions multiples of 8.
+hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, hipStream_t s);
+bool gemm_shape_ok(int M, int N, int K);
+
+// ---- attention (d = 64 or 128, S multiple of 128) ----
+hipError_t launch_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, hipStream_t s);
+hipError_t launch_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
+                                float* delta, int B, int S, int nh, int d, hipStream_t s);
+
+// ---- row-wise / element-wise kernels (bf16 I/O, fp32 math) ----
+// a = norm(x) * gamma (+ beta); stats[2*T] = (mean, rstd) per row (RMS: mean slot unused = 0)
+hipError_t launch_norm_fwd(bool rms, const void* x, const void* gamma, const void* beta, void* a, float* stats,
+                           int T, int h, float eps, hipStream_t s);
+// dx = dres + norm_bwd(da);  partial column sums of (da*xhat, da, dres) go to `part` ([3][nblk][h] fp32)
+hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float* stats, const void* gamma,
+                           const void* dres, void* dx, float* part, int T, int h, hipStream_t s);
+int norm_bwd_blocks(int T);
+// g[c] = beta * g[c] + sum_b part[b][c]
+hipError_t launch_colsum_finish(const float* part, int nblk, int n, float* g, int beta, hipStream_t s);
+// partial column sums of a bf16 matrix [T, n] -> part[nblk][n]
+hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* part, hipStream_t s);
+int colsum_blocks(int T);
+// rotary embedding in place on the Q and K blocks of qkv[T, 3*nh*d]; sign = +1 forward, -1 backward
+hipError_t launch_rope(void* qkv, const float* cos_sin, int T, int S, int nh, int d, float sign, hipStream_t s);
+// m = silu(gu[:, :F]) * gu[:, F:]
+hipError_t launch_swiglu_fwd(const void* gu, void* m, int T, int F, hipStream_t s);
+// dgu from dm and gu
+hipError_t launch_swiglu_bwd(const void* dm, const void* gu, void* dgu, int T, int F, hipStream_t s);
+
+}  // namespace ah

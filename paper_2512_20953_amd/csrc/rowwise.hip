@@ -1,0 +1,328 @@
+// Row-wise and element-wise kernels of the decoder layer: LayerNorm / RMSNorm
+// forward and backward (fused with the residual add and the column sums that
+// give the gains', offsets' and biases' gradients), column sums, rotary
+// embedding, SwiGLU.  All are bound by HBM bandwidth: every tensor is read and
+// written once, 16 bytes per lane, statistics and sums in fp32.
+#include "common.h"
+#include "kernels.h"
+
+namespace ah {
+
+namespace {
+
+constexpr int NT = 256;      // threads per block
+// MAXC (template): 16-byte chunks per thread per row, ceil(hidden / 2048), at most 8 (hidden <= 16384)
+
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();  // red may still be read from the previous call
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+__device__ __forceinline__ void block_sum2(float& a, float& b, float* red) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { red[w] = a; red[4 + w] = b; }
+  __syncthreads();
+  a = red[0] + red[1] + red[2] + red[3];
+  b = red[4] + red[5] + red[6] + red[7];
+}
+
+// ---------------------------------------------------------------- norm forward: one block per row
+template <bool RMS, int MAXC>
+__global__ __launch_bounds__(NT) void norm_fwd_kernel(const bf16* __restrict__ x, const bf16* __restrict__ gamma,
+                                                      const bf16* __restrict__ beta, bf16* __restrict__ a,
+                                                      float* __restrict__ stats, int h, float eps) {
+  __shared__ float red[8];
+  const int row = blockIdx.x, nchunk = h >> 3;
+  const bf16* xr = x + (size_t)row * h;
+  float v[MAXC][8];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXC; i++) {
+    const int c = threadIdx.x + i * NT;
+    if (c < nchunk) {
+      bf16x8 t = *(const bf16x8*)(xr + c * 8);
+#pragma unroll
+      for (int j = 0; j < 8; j++) { v[i][j] = bf2f(t[j]); s += RMS ? v[i][j] * v[i][j] : v[i][j]; }
+    }
+  }
+  float mean = 0.f, rstd;
+  if (RMS) {
+    rstd = rsqrtf(block_sum(s, red) / h + eps);
+  } else {
+    mean = block_sum(s, red) / h;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; i++)
+      if (threadIdx.x + i * NT < nchunk)
+#pragma unroll
+        for (int j = 0; j < 8; j++) { float d = v[i][j] - mean; q += d * d; }
+    rstd = rsqrtf(block_sum(q, red) / h + eps);
+  }
+  if (threadIdx.x == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
+#pragma unroll
+  for (int i = 0; i < MAXC; i++) {
+    const int c = threadIdx.x + i * NT;
+    if (c < nchunk) {
+      bf16x8 g = *(const bf16x8*)(gamma + c * 8), o;
+      bf16x8 b;
+      if (!RMS) b = *(const bf16x8*)(beta + c * 8);
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        float r = (v[i][j] - mean) * rstd * bf2f(g[j]);
+        if (!RMS) r += bf2f(b[j]);
+        o[j] = f2bf(r);
+      }
+      *(bf16x8*)(a + (size_t)row * h + c * 8) = o;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- norm backward
+// Block b handles rows [b*rpb, (b+1)*rpb); a thread keeps its columns for all of
+// them, so the three column sums accumulate in registers and leave the block once.
+template <bool RMS, int MAXC>
+__global__ __launch_bounds__(NT) void norm_bwd_kernel(const bf16* __restrict__ da, const bf16* __restrict__ x,
+                                                      const float* __restrict__ stats, const bf16* __restrict__ gamma,
+                                                      const bf16* __restrict__ dres, bf16* __restrict__ dx,
+                                                      float* __restrict__ part, int T, int h, int rpb) {
+  __shared__ float red[8];
+  const int nchunk = h >> 3, nblk = gridDim.x;
+  float gam[MAXC][8], s_g[MAXC][8], s_b[MAXC][8], s_r[MAXC][8];
+#pragma unroll
+  for (int i = 0; i < MAXC; i++) {
+    const int c = threadIdx.x + i * NT;
+    if (c < nchunk) {
+      bf16x8 g = *(const bf16x8*)(gamma + c * 8);
+#pragma unroll
+      for (int j = 0; j < 8; j++) { gam[i][j] = bf2f(g[j]); s_g[i][j] = 0.f; s_b[i][j] = 0.f; s_r[i][j] = 0.f; }
+    }
+  }
+  const int r0 = blockIdx.x * rpb, r1 = min(T, r0 + rpb);
+  for (int row = r0; row < r1; row++) {
+    const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+    float xh[MAXC][8], w[MAXC][8];
+    float sw = 0.f, swx = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; i++) {
+      const int c = threadIdx.x + i * NT;
+      if (c < nchunk) {
+        bf16x8 tx = *(const bf16x8*)(x + (size_t)row * h + c * 8);
+        bf16x8 td = *(const bf16x8*)(da + (size_t)row * h + c * 8);
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          const float d = bf2f(td[j]);
+          xh[i][j] = (bf2f(tx[j]) - mean) * rstd;
+          w[i][j] = d * gam[i][j];
+          sw += w[i][j];
+          swx += w[i][j] * xh[i][j];
+          s_g[i][j] += d * xh[i][j];
+          s_b[i][j] += d;
+        }
+      }
+    }
+    if (RMS) { swx = block_sum(swx, red); sw = 0.f; } else block_sum2(sw, swx, red);
+    const float c1 = sw / h, c2 = swx / h;
+#pragma unroll
+    for (int i = 0; i < MAXC; i++) {
+      const int c = threadIdx.x + i * NT;
+      if (c < nchunk) {
+        bf16x8 tr = *(const bf16x8*)(dres + (size_t)row * h + c * 8), o;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          const float r = bf2f(tr[j]);
+          s_r[i][j] += r;
+          o[j] = f2bf(r + rstd * (w[i][j] - c1 - xh[i][j] * c2));
+        }
+        *(bf16x8*)(dx + (size_t)row * h + c * 8) = o;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < MAXC; i++) {
+    const int c = threadIdx.x + i * NT;
+    if (c < nchunk) {
+      float* p0 = part + ((size_t)0 * nblk + blockIdx.x) * h + c * 8;
+      float* p1 = part + ((size_t)1 * nblk + blockIdx.x) * h + c * 8;
+      float* p2 = part + ((size_t)2 * nblk + blockIdx.x) * h + c * 8;
+#pragma unroll
+      for (int j = 0; j < 8; j++) { p0[j] = s_g[i][j]; p1[j] = s_b[i][j]; p2[j] = s_r[i][j]; }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- column sums
+// grid (ceil(n / 2048), nblk): thread owns 8 columns, block owns a slab of rows
+__global__ __launch_bounds__(NT) void colsum_partial_kernel(const bf16* __restrict__ m, int T, int n, int ld,
+                                                            float* __restrict__ part) {
+  const int col = (blockIdx.x * NT + threadIdx.x) * 8;
+  if (col >= n) return;
+  const int rpb = (T + gridDim.y - 1) / gridDim.y;
+  const int r0 = blockIdx.y * rpb, r1 = min(T, r0 + rpb);
+  float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int r = r0; r < r1; r++) {
+    bf16x8 t = *(const bf16x8*)(m + (size_t)r * ld + col);
+#pragma unroll
+    for (int j = 0; j < 8; j++) s[j] += bf2f(t[j]);
+  }
+  float* p = part + (size_t)blockIdx.y * n + col;
+#pragma unroll
+  for (int j = 0; j < 8; j++) p[j] = s[j];
+}
+
+__global__ __launch_bounds__(NT) void colsum_finish_kernel(const float* __restrict__ part, int nblk, int n,
+                                                           float* __restrict__ g, int beta) {
+  const int c = blockIdx.x * NT + threadIdx.x;
+  if (c >= n) return;
+  float s = 0.f;
+  for (int b = 0; b < nblk; b++) s += part[(size_t)b * n + c];
+  g[c] = beta ? g[c] + s : s;
+}
+
+// ---------------------------------------------------------------- rotary embedding
+// thread: one token, one head of Q or K, 8 pairs (i .. i+7, i + d/2 ..)
+__global__ __launch_bounds__(NT) void rope_kernel(bf16* __restrict__ qkv, const float* __restrict__ cs, int T, int S, int nh,
+                                                  int d, float sign) {
+  const int half = d >> 1, per_head = half >> 3;
+  const long idx = (long)blockIdx.x * NT + threadIdx.x;
+  const long total = (long)T * 2 * nh * per_head;
+  if (idx >= total) return;
+  const int piece = idx % per_head;
+  const int head = (idx / per_head) % (2 * nh);   // heads of Q then heads of K: contiguous in the packed row
+  const int t = idx / ((long)per_head * 2 * nh);
+  const int pos = t % S;
+  bf16* p = qkv + (size_t)t * 3 * nh * d + (size_t)head * d + piece * 8;
+  bf16x8 a = *(bf16x8*)p, b = *(bf16x8*)(p + half), oa, ob;
+  const float* c = cs + ((size_t)pos * half + piece * 8) * 2;
+#pragma unroll
+  for (int j = 0; j < 8; j++) {
+    const float co = c[2 * j], si = c[2 * j + 1] * sign;
+    const float fa = bf2f(a[j]), fb = bf2f(b[j]);
+    oa[j] = f2bf(fa * co - fb * si);
+    ob[j] = f2bf(fb * co + fa * si);
+  }
+  *(bf16x8*)p = oa;
+  *(bf16x8*)(p + half) = ob;
+}
+
+// ---------------------------------------------------------------- SwiGLU
+__global__ __launch_bounds__(NT) void swiglu_fwd_kernel(const bf16* __restrict__ gu, bf16* __restrict__ m, long n8, int F) {
+  const long idx = (long)blockIdx.x * NT + threadIdx.x;
+  if (idx >= n8) return;
+  const int per_row = F >> 3;
+  const long t = idx / per_row;
+  const int c = (idx % per_row) * 8;
+  bf16x8 g = *(const bf16x8*)(gu + t * 2 * F + c), u = *(const bf16x8*)(gu + t * 2 * F + F + c), o;
+#pragma unroll
+  for (int j = 0; j < 8; j++) {
+    const float x = bf2f(g[j]);
+    o[j] = f2bf(x / (1.f + __expf(-x)) * bf2f(u[j]));
+  }
+  *(bf16x8*)(m + t * F + c) = o;
+}
+
+__global__ __launch_bounds__(NT) void swiglu_bwd_kernel(const bf16* __restrict__ dm, const bf16* __restrict__ gu,
+                                                        bf16* __restrict__ dgu, long n8, int F) {
+  const long idx = (long)blockIdx.x * NT + threadIdx.x;
+  if (idx >= n8) return;
+  const int per_row = F >> 3;
+  const long t = idx / per_row;
+  const int c = (idx % per_row) * 8;
+  bf16x8 g = *(const bf16x8*)(gu + t * 2 * F + c), u = *(const bf16x8*)(gu + t * 2 * F + F + c);
+  bf16x8 d = *(const bf16x8*)(dm + t * F + c), og, ou;
+#pragma unroll
+  for (int j = 0; j < 8; j++) {
+    const float x = bf2f(g[j]), dd = bf2f(d[j]);
+    const float s = 1.f / (1.f + __expf(-x));
+    og[j] = f2bf(dd * bf2f(u[j]) * s * (1.f + x * (1.f - s)));
+    ou[j] = f2bf(dd * x * s);
+  }
+  *(bf16x8*)(dgu + t * 2 * F + c) = og;
+  *(bf16x8*)(dgu + t * 2 * F + F + c) = ou;
+}
+
+}  // namespace
+
+namespace {
+template <bool RMS, int MAXC>
+void norm_fwd_go(const void* x, const void* gamma, const void* beta, void* a, float* stats, int T, int h, float eps, hipStream_t s) {
+  hipLaunchKernelGGL((norm_fwd_kernel<RMS, MAXC>), dim3(T), dim3(NT), 0, s, (const bf16*)x, (const bf16*)gamma, (const bf16*)beta,
+                     (bf16*)a, stats, h, eps);
+}
+template <bool RMS, int MAXC>
+void norm_bwd_go(const void* da, const void* x, const float* stats, const void* gamma, const void* dres, void* dx, float* part,
+                 int T, int h, hipStream_t s) {
+  const int nblk = norm_bwd_blocks(T);
+  const int rpb = (T + nblk - 1) / nblk;
+  hipLaunchKernelGGL((norm_bwd_kernel<RMS, MAXC>), dim3(nblk), dim3(NT), 0, s, (const bf16*)da, (const bf16*)x, stats,
+                     (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, part, T, h, rpb);
+}
+}  // namespace
+
+int norm_bwd_blocks(int T) { return T / 4 < 256 ? (T / 4 > 0 ? T / 4 : 1) : 256; }
+
+#define AH_BY_CHUNKS(FN, RMS, ...)                                   \
+  do {                                                               \
+    const int nc = (h + 2047) / 2048;                                \
+    if (nc <= 1) FN<RMS, 1>(__VA_ARGS__);                            \
+    else if (nc == 2) FN<RMS, 2>(__VA_ARGS__);                       \
+    else if (nc == 3) FN<RMS, 3>(__VA_ARGS__);                       \
+    else if (nc == 4) FN<RMS, 4>(__VA_ARGS__);                       \
+    else FN<RMS, 8>(__VA_ARGS__);                                    \
+  } while (0)
+
+hipError_t launch_norm_fwd(bool rms, const void* x, const void* gamma, const void* beta, void* a, float* stats, int T,
+                           int h, float eps, hipStream_t s) {
+  if (h % 8 || h > 16384) return hipErrorInvalidValue;
+  if (rms) AH_BY_CHUNKS(norm_fwd_go, true, x, gamma, beta, a, stats, T, h, eps, s);
+  else AH_BY_CHUNKS(norm_fwd_go, false, x, gamma, beta, a, stats, T, h, eps, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float* stats, const void* gamma, const void* dres,
+                           void* dx, float* part, int T, int h, hipStream_t s) {
+  if (h % 8 || h > 16384) return hipErrorInvalidValue;
+  if (rms) AH_BY_CHUNKS(norm_bwd_go, true, da, x, stats, gamma, dres, dx, part, T, h, s);
+  else AH_BY_CHUNKS(norm_bwd_go, false, da, x, stats, gamma, dres, dx, part, T, h, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum_finish(const float* part, int nblk, int n, float* g, int beta, hipStream_t s) {
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, s, part, nblk, n, g, beta);
+  return hipGetLastError();
+}
+
+int colsum_blocks(int T) { return T / 16 < 64 ? (T / 16 > 0 ? T / 16 : 1) : 64; }
+
+hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* part, hipStream_t s) {
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3((n + NT * 8 - 1) / (NT * 8), colsum_blocks(T)), dim3(NT), 0, s,
+                     (const bf16*)m, T, n, ld, part);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope(void* qkv, const float* cos_sin, int T, int S, int nh, int d, float sign, hipStream_t s) {
+  const long total = (long)T * 2 * nh * (d / 16);
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((total + NT - 1) / NT)), dim3(NT), 0, s, (bf16*)qkv, cos_sin, T, S, nh, d, sign);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_fwd(const void* gu, void* m, int T, int F, hipStream_t s) {
+  const long n8 = (long)T * F / 8;
+  hipLaunchKernelGGL(swiglu_fwd_kernel, dim3((unsigned)((n8 + NT - 1) / NT)), dim3(NT), 0, s, (const bf16*)gu, (bf16*)m, n8, F);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_bwd(const void* dm, const void* gu, void* dgu, int T, int F, hipStream_t s) {
+  const long n8 = (long)T * F / 8;
+  hipLaunchKernelGGL(swiglu_bwd_kernel, dim3((unsigned)((n8 + NT - 1) / NT)), dim3(NT), 0, s, (const bf16*)dm, (const bf16*)gu,
+                     (bf16*)dgu, n8, F);
+  return hipGetLastError();
+}
+
+}  // namespace ah

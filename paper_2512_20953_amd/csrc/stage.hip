@@ -1,0 +1,502 @@
+// Stage object: buffer partitioning, the per-layer kernel sequences of forward
+// and backward, gradient accumulation state, and the profiler.  C ABI in
+// include/ah_stage.h.  Host code only enqueues kernels on the caller's stream.
+#include "ah_stage.h"
+#include "capi_util.h"
+#include "kernels.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace ah;
+
+namespace {
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct ParamEntry { uint64_t off; int rows, cols; };  // cols == 0: tensor absent in this architecture
+
+// byte offsets of one layer's saved activations
+struct ActLayout {
+  size_t x_in, a, qkv, o, lse, x_mid, c, u, g, stats1, stats2, bytes;
+};
+
+struct Workspace {
+  size_t d0, d1, dmid, dbig, dsm, delta, part, rope, prof_x, prof_dy, prof_y, prof_dx, layer_ws, bytes;
+};
+
+}  // namespace
+
+struct ah_stage {
+  ah_stage_config_t cfg;
+  ah_stage_buffers_t bufs;
+  int T, h, nh, d, hl, F, L;
+  bool llama, recompute;
+  float eps, rope_base;
+  ParamEntry ptab[AH_P_COUNT];
+  uint64_t layer_elems;
+  ActLayout act;       // offsets inside one layer's block (x_in first)
+  size_t slot_bytes;   // per in-flight micro-batch
+  size_t per_layer_slot_bytes;
+  Workspace ws;
+  std::vector<char> busy;
+  bool overwrite_grads;  // next backward writes instead of adding
+  bool rope_ready;
+};
+
+namespace {
+
+int validate(const ah_stage_config_t* c) {
+  if (!c) return set_error(AH_EINVAL, "config is NULL");
+  if (c->struct_size != sizeof(ah_stage_config_t)) return set_error(AH_EINVAL, "config.struct_size %u != %zu", c->struct_size, sizeof(ah_stage_config_t));
+  if (c->arch != AH_ARCH_GPT && c->arch != AH_ARCH_LLAMA) return set_error(AH_EINVAL, "unknown arch %d", c->arch);
+  if (c->n_layers < 1 || c->n_layers > 1024) return set_error(AH_EINVAL, "n_layers %d out of range [1, 1024]", c->n_layers);
+  if (c->tp_degree < 1 || c->tp_rank < 0 || c->tp_rank >= c->tp_degree) return set_error(AH_EINVAL, "bad tp_degree/tp_rank %d/%d", c->tp_degree, c->tp_rank);
+  if (c->n_heads < 1 || c->ffn_hidden < 1 || c->hidden < 1 || c->seq_len < 1 || c->microbatch_size < 1)
+    return set_error(AH_EINVAL, "sizes must be positive");
+  if (c->n_heads % c->tp_degree || c->ffn_hidden % c->tp_degree) return set_error(AH_EINVAL, "tp_degree must divide n_heads and ffn_hidden");
+  if (c->n_microbatches < 1) return set_error(AH_EINVAL, "n_microbatches must be >= 1");
+  if (c->max_in_flight < 1 || c->max_in_flight > 4096) return set_error(AH_EINVAL, "max_in_flight %d out of range [1, 4096]", c->max_in_flight);
+  if (c->recompute != 0 && c->recompute != 1) return set_error(AH_EINVAL, "recompute must be 0 or 1");
+  if (c->norm_eps < 0 || c->rope_base < 0) return set_error(AH_EINVAL, "norm_eps and rope_base must be >= 0");
+  if (c->head_dim != 64 && c->head_dim != 128) return set_error(AH_EUNSUPPORTED, "head_dim %d: only 64 and 128 are supported", c->head_dim);
+  if (c->hidden % 128 || c->hidden > 16384) return set_error(AH_EUNSUPPORTED, "hidden %d must be a multiple of 128 and <= 16384", c->hidden);
+  if (c->seq_len % 128) return set_error(AH_EUNSUPPORTED, "seq_len %d must be a multiple of 128", c->seq_len);
+  const long hl = (long)(c->n_heads / c->tp_degree) * c->head_dim, F = c->ffn_hidden / c->tp_degree;
+  if (hl % 128 || F % 128) return set_error(AH_EUNSUPPORTED, "local attention width %ld and local FFN width %ld must be multiples of 128", hl, F);
+  if ((long)c->microbatch_size * c->seq_len > (1L << 24)) return set_error(AH_EUNSUPPORTED, "microbatch_size * seq_len too large");
+  if (hl > 65536 || F > 262144) return set_error(AH_EUNSUPPORTED, "local widths too large");
+  return AH_OK;
+}
+
+void plan(ah_stage* s, const ah_stage_config_t* c) {
+  s->cfg = *c;
+  s->L = c->n_layers;
+  s->h = c->hidden;
+  s->nh = c->n_heads / c->tp_degree;
+  s->d = c->head_dim;
+  s->hl = s->nh * s->d;
+  s->F = c->ffn_hidden / c->tp_degree;
+  s->T = c->microbatch_size * c->seq_len;
+  s->llama = c->arch == AH_ARCH_LLAMA;
+  s->recompute = c->recompute != 0;
+  s->eps = c->norm_eps > 0 ? c->norm_eps : (s->llama ? 1e-6f : 1e-5f);
+  s->rope_base = c->rope_base > 0 ? c->rope_base : 10000.f;
+  const int h = s->h, hl = s->hl, F = s->F;
+  const size_t T = s->T;
+
+  // ---- parameters: every tensor starts on a 128-element boundary (sizes are multiples of 128)
+  uint64_t off = 0;
+  auto put = [&](int which, int rows, int cols) {
+    s->ptab[which] = {off, rows, cols};
+    off += (uint64_t)rows * cols;
+  };
+  for (auto& e : s->ptab) e = {0, 0, 0};
+  if (!s->llama) {
+    put(AH_P_LN1_G, 1, h); put(AH_P_LN1_B, 1, h); put(AH_P_WQKV, h, 3 * hl); put(AH_P_BQKV, 1, 3 * hl);
+    put(AH_P_WO, hl, h); put(AH_P_BO, 1, h); put(AH_P_LN2_G, 1, h); put(AH_P_LN2_B, 1, h);
+    put(AH_P_W1, h, F); put(AH_P_B1, 1, F); put(AH_P_W2, F, h); put(AH_P_B2, 1, h);
+  } else {
+    put(AH_P_LN1_G, 1, h); put(AH_P_WQKV, h, 3 * hl); put(AH_P_WO, hl, h); put(AH_P_LN2_G, 1, h);
+    put(AH_P_W1, h, 2 * F); put(AH_P_W2, F, h);
+  }
+  s->layer_elems = off;
+
+  // ---- activations saved for backward, per layer
+  const size_t Fu = s->llama ? 2 * (size_t)F : (size_t)F;  // width of the first MLP product
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o += align256(bytes); return r; };
+  ActLayout& a = s->act;
+  a.x_in = take(T * h * 2);
+  const size_t keep_only_input = o;
+  a.a = take(T * h * 2);
+  a.qkv = take(T * 3 * hl * 2);
+  a.o = take(T * hl * 2);
+  a.lse = take(T * s->nh * 4);
+  a.x_mid = take(T * h * 2);
+  a.c = take(T * h * 2);
+  a.u = take(T * Fu * 2);
+  a.g = take(T * F * 2);
+  a.stats1 = take(T * 2 * 4);
+  a.stats2 = take(T * 2 * 4);
+  a.bytes = o;
+  s->per_layer_slot_bytes = s->recompute ? keep_only_input : a.bytes;
+  s->slot_bytes = s->per_layer_slot_bytes * s->L;
+
+  // ---- workspace
+  Workspace& w = s->ws;
+  o = 0;
+  w.d0 = take(T * h * 2);
+  w.d1 = take(T * h * 2);
+  w.dmid = take(T * h * 2);
+  w.dbig = take(T * std::max<size_t>(Fu, 3 * hl) * 2);
+  w.dsm = take(T * std::max<size_t>({(size_t)h, (size_t)hl, (size_t)F}) * 2);
+  w.delta = take(T * s->nh * 4);
+  const size_t part_elems = std::max<size_t>((size_t)3 * norm_bwd_blocks(s->T) * h, (size_t)colsum_blocks(s->T) * std::max<size_t>(Fu, 3 * hl));
+  w.part = take(part_elems * 4);
+  w.rope = take(s->llama ? (size_t)c->seq_len * s->d * 4 : 0);
+  w.prof_x = take(T * h * 2);
+  w.prof_dy = take(T * h * 2);
+  w.prof_y = take(T * h * 2);
+  w.prof_dx = take(T * h * 2);
+  w.layer_ws = take(s->recompute ? a.bytes : 0);
+  w.bytes = o;
+}
+
+inline char* P(void* base, size_t off) { return (char*)base + off; }
+
+// ------------------------------------------------------------------ small device helpers
+__global__ void rope_table_kernel(float* cs, int S, int half, int d, double base) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= S * half) return;
+  const int pos = idx / half, i = idx % half;
+  const double theta = exp(-(2.0 * i / d) * log(base));
+  const double ang = pos * theta;
+  cs[2 * idx] = (float)cos(ang);
+  cs[2 * idx + 1] = (float)sin(ang);
+}
+
+__global__ void fill_pattern_kernel(__bf16* p, size_t n, uint32_t seed) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  uint32_t x = (uint32_t)i * 2654435761u + seed;
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  p[i] = (__bf16)(((x & 0xffff) / 65536.0f - 0.5f) * 3.4641f);  // uniform, unit variance
+}
+
+struct LayerPtrs {
+  const char *ln1_g, *ln1_b, *wqkv, *bqkv, *wo, *bo, *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
+  float *g_ln1_g, *g_ln1_b, *g_wqkv, *g_bqkv, *g_wo, *g_bo, *g_ln2_g, *g_ln2_b, *g_w1, *g_b1, *g_w2, *g_b2;
+};
+
+LayerPtrs layer_ptrs(const ah_stage* s, int layer) {
+  LayerPtrs p;
+  const char* pb = (const char*)s->bufs.params + (size_t)layer * s->layer_elems * 2;
+  float* gb = (float*)s->bufs.grads + (size_t)layer * s->layer_elems;
+  auto pp = [&](int w) -> const char* { return s->ptab[w].cols ? pb + s->ptab[w].off * 2 : nullptr; };
+  auto gp = [&](int w) -> float* { return s->ptab[w].cols ? gb + s->ptab[w].off : nullptr; };
+  p.ln1_g = pp(AH_P_LN1_G); p.ln1_b = pp(AH_P_LN1_B); p.wqkv = pp(AH_P_WQKV); p.bqkv = pp(AH_P_BQKV);
+  p.wo = pp(AH_P_WO); p.bo = pp(AH_P_BO); p.ln2_g = pp(AH_P_LN2_G); p.ln2_b = pp(AH_P_LN2_B);
+  p.w1 = pp(AH_P_W1); p.b1 = pp(AH_P_B1); p.w2 = pp(AH_P_W2); p.b2 = pp(AH_P_B2);
+  p.g_ln1_g = gp(AH_P_LN1_G); p.g_ln1_b = gp(AH_P_LN1_B); p.g_wqkv = gp(AH_P_WQKV); p.g_bqkv = gp(AH_P_BQKV);
+  p.g_wo = gp(AH_P_WO); p.g_bo = gp(AH_P_BO); p.g_ln2_g = gp(AH_P_LN2_G); p.g_ln2_b = gp(AH_P_LN2_B);
+  p.g_w1 = gp(AH_P_W1); p.g_b1 = gp(AH_P_B1); p.g_w2 = gp(AH_P_W2); p.g_b2 = gp(AH_P_B2);
+  return p;
+}
+
+// pointers to one layer's activations: the input always lives in the slot; the
+// rest either in the slot (stored) or in the shared per-layer scratch (recompute)
+struct ActPtrs { char *x_in, *a, *qkv, *o, *lse, *x_mid, *c, *u, *g, *stats1, *stats2; };
+
+ActPtrs act_ptrs(const ah_stage* s, int slot, int layer) {
+  char* slot_base = (char*)s->bufs.activations + (size_t)slot * s->slot_bytes + (size_t)layer * s->per_layer_slot_bytes;
+  char* rest = s->recompute ? (char*)s->bufs.workspace + s->ws.layer_ws : slot_base;
+  const ActLayout& a = s->act;
+  ActPtrs p;
+  p.x_in = slot_base + a.x_in;
+  p.a = rest + a.a; p.qkv = rest + a.qkv; p.o = rest + a.o; p.lse = rest + a.lse; p.x_mid = rest + a.x_mid;
+  p.c = rest + a.c; p.u = rest + a.u; p.g = rest + a.g; p.stats1 = rest + a.stats1; p.stats2 = rest + a.stats2;
+  return p;
+}
+
+#define TRY(expr)                        \
+  do {                                   \
+    hipError_t e_ = (expr);              \
+    if (e_ != hipSuccess) return e_;     \
+  } while (0)
+
+hipError_t gemm(GemmLayout lay, GemmEpilogue epi, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N,
+                int K, const void* bias, const void* aux, int ld_aux, void* C2, int beta, hipStream_t st) {
+  GemmArgs g = {};
+  g.A = A; g.B = B; g.C = C; g.C2 = C2; g.bias = bias; g.aux = aux;
+  g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ld_aux = ld_aux; g.M = M; g.N = N; g.K = K; g.beta = beta;
+  return launch_gemm(lay, epi, g, st);
+}
+
+// One layer forward.  y == nullptr: stop after the activations backward needs
+// (used when a layer is re-run inside backward).
+hipError_t layer_forward(ah_stage* s, int layer, const ActPtrs& a, void* y, hipStream_t st) {
+  const LayerPtrs p = layer_ptrs(s, layer);
+  const int T = s->T, h = s->h, hl = s->hl, F = s->F, B = s->cfg.microbatch_size, S = s->cfg.seq_len;
+  TRY(launch_norm_fwd(s->llama, a.x_in, p.ln1_g, p.ln1_b, a.a, (float*)a.stats1, T, h, s->eps, st));
+  TRY(gemm(GEMM_NN, EPI_BF16, a.a, h, p.wqkv, 3 * hl, a.qkv, 3 * hl, T, 3 * hl, h, p.bqkv, nullptr, 0, nullptr, 0, st));
+  if (s->llama) TRY(launch_rope(a.qkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, 1.f, st));
+  TRY(launch_attention_fwd(a.qkv, a.o, (float*)a.lse, B, S, s->nh, s->d, st));
+  TRY(gemm(GEMM_NN, EPI_RESID, a.o, hl, p.wo, h, a.x_mid, h, T, h, hl, p.bo, a.x_in, h, nullptr, 0, st));
+  TRY(launch_norm_fwd(s->llama, a.x_mid, p.ln2_g, p.ln2_b, a.c, (float*)a.stats2, T, h, s->eps, st));
+  if (!s->llama) {
+    TRY(gemm(GEMM_NN, EPI_GELU, a.c, h, p.w1, F, a.u, F, T, F, h, p.b1, nullptr, 0, a.g, 0, st));
+  } else {
+    TRY(gemm(GEMM_NN, EPI_BF16, a.c, h, p.w1, 2 * F, a.u, 2 * F, T, 2 * F, h, nullptr, nullptr, 0, nullptr, 0, st));
+    TRY(launch_swiglu_fwd(a.u, a.g, T, F, st));
+  }
+  if (y) TRY(gemm(GEMM_NN, EPI_RESID, a.g, F, p.w2, h, y, h, T, h, F, p.b2, a.x_mid, h, nullptr, 0, st));
+  return hipSuccess;
+}
+
+hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, int beta, hipStream_t st) {
+  const LayerPtrs p = layer_ptrs(s, layer);
+  const int T = s->T, h = s->h, hl = s->hl, F = s->F, B = s->cfg.microbatch_size, S = s->cfg.seq_len;
+  char* wsb = (char*)s->bufs.workspace;
+  char *dmid = wsb + s->ws.dmid, *dbig = wsb + s->ws.dbig, *dsm = wsb + s->ws.dsm;
+  float* part = (float*)(wsb + s->ws.part);
+  float* delta = (float*)(wsb + s->ws.delta);
+  const int nb = norm_bwd_blocks(T), cb = colsum_blocks(T);
+  const bool rms = s->llama;
+
+  // second MLP matrix: dW2 += g^T dy ; input gradient of the activation
+  TRY(gemm(GEMM_TN, EPI_F32_ACC, a.g, F, dy, h, p.g_w2, h, F, h, T, nullptr, nullptr, 0, nullptr, beta, st));
+  if (!s->llama) {
+    TRY(gemm(GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, dbig, F, T, F, h, nullptr, a.u, F, nullptr, 0, st));  // du
+    TRY(launch_colsum_partial(dbig, T, F, F, part, st));
+    TRY(launch_colsum_finish(part, cb, F, p.g_b1, beta, st));
+    TRY(gemm(GEMM_TN, EPI_F32_ACC, a.c, h, dbig, F, p.g_w1, F, h, F, T, nullptr, nullptr, 0, nullptr, beta, st));
+    TRY(gemm(GEMM_NT, EPI_BF16, dbig, F, p.w1, F, dsm, h, T, h, F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
+  } else {
+    TRY(gemm(GEMM_NT, EPI_BF16, dy, h, p.w2, h, dsm, F, T, F, h, nullptr, nullptr, 0, nullptr, 0, st));  // dm
+    TRY(launch_swiglu_bwd(dsm, a.u, dbig, T, F, st));                                                     // d(gate|up)
+    TRY(gemm(GEMM_TN, EPI_F32_ACC, a.c, h, dbig, 2 * F, p.g_w1, 2 * F, h, 2 * F, T, nullptr, nullptr, 0, nullptr, beta, st));
+    TRY(gemm(GEMM_NT, EPI_BF16, dbig, 2 * F, p.w1, 2 * F, dsm, h, T, h, 2 * F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
+  }
+  // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
+  TRY(launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part, T, h, st));
+  TRY(launch_colsum_finish(part, nb, h, p.g_ln2_g, beta, st));
+  if (!rms) {
+    TRY(launch_colsum_finish(part + (size_t)nb * h, nb, h, p.g_ln2_b, beta, st));
+    TRY(launch_colsum_finish(part + (size_t)2 * nb * h, nb, h, p.g_b2, beta, st));
+  }
+  // output projection
+  TRY(gemm(GEMM_TN, EPI_F32_ACC, a.o, hl, dmid, h, p.g_wo, h, hl, h, T, nullptr, nullptr, 0, nullptr, beta, st));
+  TRY(gemm(GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
+  // attention
+  TRY(launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dbig, delta, B, S, s->nh, s->d, st));
+  if (s->llama) TRY(launch_rope(dbig, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
+  if (!s->llama) {
+    TRY(launch_colsum_partial(dbig, T, 3 * hl, 3 * hl, part, st));
+    TRY(launch_colsum_finish(part, cb, 3 * hl, p.g_bqkv, beta, st));
+  }
+  TRY(gemm(GEMM_TN, EPI_F32_ACC, a.a, h, dbig, 3 * hl, p.g_wqkv, 3 * hl, h, 3 * hl, T, nullptr, nullptr, 0, nullptr, beta, st));
+  TRY(gemm(GEMM_NT, EPI_BF16, dbig, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
+  // first norm backward; dx = dx_mid + norm_bwd(da); column sums give d(gain), d(offset), d(bo)
+  TRY(launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part, T, h, st));
+  TRY(launch_colsum_finish(part, nb, h, p.g_ln1_g, beta, st));
+  if (!rms) {
+    TRY(launch_colsum_finish(part + (size_t)nb * h, nb, h, p.g_ln1_b, beta, st));
+    TRY(launch_colsum_finish(part + (size_t)2 * nb * h, nb, h, p.g_bo, beta, st));
+  }
+  return hipSuccess;
+}
+
+hipError_t ensure_rope(ah_stage* s, hipStream_t st) {
+  if (!s->llama || s->rope_ready) return hipSuccess;
+  const int S = s->cfg.seq_len, half = s->d / 2;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((S * half + 255) / 256), dim3(256), 0, st, (float*)P(s->bufs.workspace, s->ws.rope), S,
+                     half, s->d, (double)s->rope_base);
+  s->rope_ready = true;
+  return hipGetLastError();
+}
+
+hipError_t stage_forward(ah_stage* s, int slot, const void* x, void* y, hipStream_t st, hipEvent_t* ev) {
+  TRY(ensure_rope(s, st));
+  const size_t xbytes = (size_t)s->T * s->h * 2;
+  TRY(hipMemcpyAsync(act_ptrs(s, slot, 0).x_in, x, xbytes, hipMemcpyDeviceToDevice, st));
+  if (ev) TRY(hipEventRecord(ev[0], st));
+  for (int l = 0; l < s->L; l++) {
+    const ActPtrs a = act_ptrs(s, slot, l);
+    void* out = (l + 1 < s->L) ? (void*)act_ptrs(s, slot, l + 1).x_in : y;
+    TRY(layer_forward(s, l, a, out, st));
+    if (ev) TRY(hipEventRecord(ev[l + 1], st));
+  }
+  return hipSuccess;
+}
+
+hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipStream_t st, hipEvent_t* ev) {
+  const int beta = s->overwrite_grads ? 0 : 1;
+  char* wsb = (char*)s->bufs.workspace;
+  const void* cur = dy;
+  if (ev) TRY(hipEventRecord(ev[s->L], st));
+  for (int l = s->L - 1; l >= 0; l--) {
+    const ActPtrs a = act_ptrs(s, slot, l);
+    if (s->recompute) TRY(layer_forward(s, l, a, nullptr, st));
+    void* out = (l == 0) ? dx : (void*)(wsb + ((l & 1) ? s->ws.d1 : s->ws.d0));
+    TRY(layer_backward(s, l, a, cur, out, beta, st));
+    cur = out;
+    if (ev) TRY(hipEventRecord(ev[l], st));
+  }
+  s->overwrite_grads = false;
+  return hipSuccess;
+}
+
+float median(std::vector<float>& v) {
+  std::sort(v.begin(), v.end());
+  return v.empty() ? 0.f : v[v.size() / 2];
+}
+
+}  // namespace
+
+extern "C" int ah_stage_query_sizes(const ah_stage_config_t* cfg, ah_stage_sizes_t* out) {
+  if (!out) return set_error(AH_EINVAL, "ah_stage_query_sizes: out is NULL");
+  int rc = validate(cfg);
+  if (rc) return rc;
+  ah_stage tmp;
+  plan(&tmp, cfg);
+  out->param_elems = tmp.layer_elems * tmp.L;
+  out->param_bytes = out->param_elems * 2;
+  out->grad_bytes = out->param_elems * 4;
+  out->activation_bytes_per_slot = tmp.slot_bytes;
+  out->activation_bytes_per_layer_per_slot = tmp.per_layer_slot_bytes;
+  out->workspace_bytes = tmp.ws.bytes;
+  return AH_OK;
+}
+
+extern "C" int ah_stage_create(const ah_stage_config_t* cfg, const ah_stage_buffers_t* bufs, ah_stage_t** out) {
+  if (!out) return set_error(AH_EINVAL, "ah_stage_create: out is NULL");
+  *out = nullptr;
+  int rc = validate(cfg);
+  if (rc) return rc;
+  if (!bufs || !bufs->params || !bufs->grads || !bufs->activations || !bufs->workspace)
+    return set_error(AH_EINVAL, "ah_stage_create: all four buffers are required");
+  if (((uintptr_t)bufs->params | (uintptr_t)bufs->grads | (uintptr_t)bufs->activations | (uintptr_t)bufs->workspace) & 255)
+    return set_error(AH_EINVAL, "ah_stage_create: buffers must be 256-byte aligned");
+  ah_stage* s = new (std::nothrow) ah_stage();
+  if (!s) return set_error(AH_ENOMEM, "ah_stage_create: out of host memory");
+  plan(s, cfg);
+  s->bufs = *bufs;
+  s->busy.assign(cfg->max_in_flight, 0);
+  s->overwrite_grads = true;
+  s->rope_ready = false;
+  *out = s;
+  return AH_OK;
+}
+
+extern "C" int ah_stage_destroy(ah_stage_t* st) {
+  delete st;
+  return AH_OK;
+}
+
+extern "C" int ah_stage_param_layout(const ah_stage_t* st, int layer, int which, uint64_t* elem_offset, int32_t* rows, int32_t* cols) {
+  if (!st || !elem_offset || !rows || !cols) return set_error(AH_EINVAL, "ah_stage_param_layout: NULL argument");
+  if (layer < 0 || layer >= st->L || which < 0 || which >= AH_P_COUNT) return set_error(AH_EINVAL, "ah_stage_param_layout: layer %d / tensor %d out of range", layer, which);
+  if (!st->ptab[which].cols) return set_error(AH_EINVAL, "ah_stage_param_layout: tensor %d does not exist in this architecture", which);
+  *elem_offset = (uint64_t)layer * st->layer_elems + st->ptab[which].off;
+  *rows = st->ptab[which].rows;
+  *cols = st->ptab[which].cols;
+  return AH_OK;
+}
+
+extern "C" int ah_stage_forward(ah_stage_t* st, int slot, const void* x, void* y, void* stream) {
+  if (!st || !x || !y) return set_error(AH_EINVAL, "ah_stage_forward: NULL argument");
+  if (slot < 0 || slot >= (int)st->busy.size()) return set_error(AH_EINVAL, "ah_stage_forward: slot %d out of range [0, %zu)", slot, st->busy.size());
+  if (st->busy[slot]) return set_error(AH_ESTATE, "ah_stage_forward: slot %d still holds a micro-batch awaiting backward", slot);
+  int rc = hip_status(stage_forward(st, slot, x, y, (hipStream_t)stream, nullptr), "ah_stage_forward");
+  if (rc == AH_OK) st->busy[slot] = 1;
+  return rc;
+}
+
+extern "C" int ah_stage_backward(ah_stage_t* st, int slot, const void* dy, void* dx, void* stream) {
+  if (!st || !dy || !dx) return set_error(AH_EINVAL, "ah_stage_backward: NULL argument");
+  if (slot < 0 || slot >= (int)st->busy.size()) return set_error(AH_EINVAL, "ah_stage_backward: slot %d out of range [0, %zu)", slot, st->busy.size());
+  if (!st->busy[slot]) return set_error(AH_ESTATE, "ah_stage_backward: slot %d holds no forward pass", slot);
+  int rc = hip_status(stage_backward(st, slot, dy, dx, (hipStream_t)stream, nullptr), "ah_stage_backward");
+  if (rc == AH_OK) st->busy[slot] = 0;
+  return rc;
+}
+
+extern "C" int ah_stage_grads(ah_stage_t* st, float** dev_ptr, uint64_t* n_elems) {
+  if (!st || !dev_ptr || !n_elems) return set_error(AH_EINVAL, "ah_stage_grads: NULL argument");
+  *dev_ptr = (float*)st->bufs.grads;
+  *n_elems = st->layer_elems * st->L;
+  return AH_OK;
+}
+
+extern "C" int ah_stage_zero_grads(ah_stage_t* st, void* /*stream*/) {
+  if (!st) return set_error(AH_EINVAL, "ah_stage_zero_grads: NULL argument");
+  st->overwrite_grads = true;
+  return AH_OK;
+}
+
+extern "C" int ah_stage_profile(ah_stage_t* st, int warmup, int iters, ah_stage_profile_t* out) {
+  if (!st || !out) return set_error(AH_EINVAL, "ah_stage_profile: NULL argument");
+  if (out->struct_size != sizeof(ah_stage_profile_t)) return set_error(AH_EINVAL, "ah_stage_profile: struct_size mismatch");
+  if (out->n_layers < st->L || !out->fwd_ms || !out->bwd_ms) return set_error(AH_EINVAL, "ah_stage_profile: fwd_ms/bwd_ms must hold n_layers entries");
+  if (warmup < 0 || iters < 1 || iters > 10000) return set_error(AH_EINVAL, "ah_stage_profile: warmup >= 0 and 1 <= iters <= 10000 required");
+  for (char b : st->busy)
+    if (b) return set_error(AH_ESTATE, "ah_stage_profile: all slots must be empty");
+  const int L = st->L, K = st->cfg.n_microbatches;
+  char* wsb = (char*)st->bufs.workspace;
+  __bf16* px = (__bf16*)(wsb + st->ws.prof_x);
+  __bf16* pdy = (__bf16*)(wsb + st->ws.prof_dy);
+  const size_t n = (size_t)st->T * st->h;
+  hipStream_t s = nullptr;
+  std::vector<hipEvent_t> ef(L + 1), eb(L + 1);
+  hipEvent_t it0, it1;
+  hipError_t e = hipSuccess;
+  for (auto& v : ef) if (e == hipSuccess) e = hipEventCreate(&v);
+  for (auto& v : eb) if (e == hipSuccess) e = hipEventCreate(&v);
+  if (e == hipSuccess) e = hipEventCreate(&it0);
+  if (e == hipSuccess) e = hipEventCreate(&it1);
+  if (e != hipSuccess) return hip_status(e, "ah_stage_profile (events)");
+  hipLaunchKernelGGL(fill_pattern_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, px, n, 1u);
+  hipLaunchKernelGGL(fill_pattern_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, pdy, n, 2u);
+  void* y = wsb + st->ws.prof_y;
+  void* dx = wsb + st->ws.prof_dx;
+  std::vector<std::vector<float>> tf(L), tb(L);
+  std::vector<float> sf, sb, ti;
+  for (int it = 0; it < warmup + iters && e == hipSuccess; it++) {
+    st->overwrite_grads = true;
+    e = stage_forward(st, 0, px, y, s, ef.data());
+    if (e == hipSuccess) e = stage_backward(st, 0, pdy, dx, s, eb.data());
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess || it < warmup) continue;
+    float ms;
+    for (int l = 0; l < L; l++) {
+      (void)hipEventElapsedTime(&ms, ef[l], ef[l + 1]); tf[l].push_back(ms);
+      (void)hipEventElapsedTime(&ms, eb[l + 1], eb[l]); tb[l].push_back(ms);
+    }
+    (void)hipEventElapsedTime(&ms, ef[0], ef[L]); sf.push_back(ms);
+    (void)hipEventElapsedTime(&ms, eb[L], eb[0]); sb.push_back(ms);
+  }
+  for (int it = 0; it < std::min(warmup, 2) + iters && e == hipSuccess; it++) {
+    st->overwrite_grads = true;
+    e = hipEventRecord(it0, s);
+    for (int k = 0; k < K && e == hipSuccess; k++) {
+      e = stage_forward(st, 0, px, y, s, nullptr);
+      if (e == hipSuccess) e = stage_backward(st, 0, pdy, dx, s, nullptr);
+    }
+    if (e == hipSuccess) e = hipEventRecord(it1, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    float ms;
+    if (e == hipSuccess && it >= std::min(warmup, 2)) { (void)hipEventElapsedTime(&ms, it0, it1); ti.push_back(ms); }
+  }
+  for (auto& v : ef) (void)hipEventDestroy(v);
+  for (auto& v : eb) (void)hipEventDestroy(v);
+  (void)hipEventDestroy(it0);
+  (void)hipEventDestroy(it1);
+  st->overwrite_grads = true;
+  if (e != hipSuccess) return hip_status(e, "ah_stage_profile");
+  for (int l = 0; l < L; l++) { out->fwd_ms[l] = median(tf[l]); out->bwd_ms[l] = median(tb[l]); }
+  out->stage_fwd_ms = median(sf);
+  out->stage_bwd_ms = median(sb);
+  out->iteration_ms = median(ti);
+  out->peak_activation_bytes = (uint64_t)st->busy.size() * st->slot_bytes + st->ws.bytes;
+  out->activation_bytes_per_layer_per_slot = st->per_layer_slot_bytes;
+  out->param_bytes = st->layer_elems * st->L * 2;
+  out->grad_bytes = st->layer_elems * st->L * 4;
+  return AH_OK;
+}
+
+extern "C" int ah_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, void* stream) {
+  if (!qkv || !o || !lse) return set_error(AH_EINVAL, "ah_attention_fwd: NULL pointer");
+  if (B < 1 || nh < 1 || S < 1 || S % 128 || (d != 64 && d != 128)) return set_error(AH_EUNSUPPORTED, "ah_attention_fwd: need S %% 128 == 0 and d in {64, 128}");
+  return hip_status(launch_attention_fwd(qkv, o, lse, B, S, nh, d, (hipStream_t)stream), "ah_attention_fwd");
+}
+
+extern "C" int ah_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta, int B,
+                                int S, int nh, int d, void* stream) {
+  if (!qkv || !o || !lse || !d_o || !dqkv || !delta) return set_error(AH_EINVAL, "ah_attention_bwd: NULL pointer");
+  if (B < 1 || nh < 1 || S < 1 || S % 128 || (d != 64 && d != 128)) return set_error(AH_EUNSUPPORTED, "ah_attention_bwd: need S %% 128 == 0 and d in {64, 128}");
+  return hip_status(launch_attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, (hipStream_t)stream), "ah_attention_bwd");
+}

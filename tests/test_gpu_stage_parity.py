@@ -1,0 +1,155 @@
+"""HIP stage vs CPU oracle, through the C ABI, on the same seeded inputs.
+
+Tolerances (normalised L2 per tensor): activations 2e-2, gradients 3e-2; index
+and mask work (causality, slot bookkeeping, recompute, determinism) bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_20953_amd as P
+from synth import stage_inputs as SI
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(w, n_mb=None, perturb=True):
+    params = [SI.draw_layer_params(w, l, perturb_vectors=perturb) for l in range(w["n_layers"])]
+    k = w["n_mb"] if n_mb is None else n_mb
+    xs = [SI.draw_activation(w, "x", m) for m in range(k)]
+    dys = [SI.draw_activation(w, "dy", m) for m in range(k)]
+    return params, xs, dys
+
+
+def _run_case(w, n_mb=None, perturb=True, oracle_dtype=np.float64, **kw):
+    gcfg, ocfg = U.make_cfgs(w, **kw)
+    params, xs, dys = _inputs(w, n_mb, perturb)
+    st = P.Stage(gcfg)
+    U.load_params(st, params)
+    ys, dxs = U.run_gpu(st, xs, dys)
+    o_ys, o_dxs, o_grads = U.run_oracle(ocfg, params, xs, dys, oracle_dtype)
+    wa, wg = U.compare_stage(st, params, ys, dxs, o_ys, o_dxs, o_grads)
+    print("worst activation err %.3e, worst gradient err %.3e" % (wa, wg))
+    return st, ys, dxs
+
+
+def test_tiny_stage_as_specified():
+    """Workload 'tiny' exactly as in the workload table (biases 0, gains 1), all K micro-batches."""
+    _run_case(SI.WORKLOADS["tiny"], perturb=False)
+
+
+def test_tiny_stage_with_nonzero_vectors():
+    """Same shapes, biases / gains / offsets perturbed so their paths are visible."""
+    _run_case(SI.WORKLOADS["tiny"])
+
+
+REDUCED = {
+    # several tiles in every GEMM dimension, 3 query blocks, head_dim 128, TP shard
+    "gpt_d128_tp2": dict(arch="gpt", n_layers=2, hidden=384, n_heads=4, head_dim=128, ffn=1536, seq=384, mb=2, n_mb=3, tp=2, recompute=0),
+    "llama_small": dict(arch="llama", n_layers=2, hidden=512, n_heads=4, head_dim=128, ffn=768, seq=256, mb=1, n_mb=2, tp=1, recompute=0),
+    "llama_d64": dict(arch="llama", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=384, seq=128, mb=2, n_mb=2, tp=1, recompute=0),
+}
+
+
+@pytest.mark.parametrize("name", list(REDUCED))
+def test_reduced_stages(name):
+    _run_case(REDUCED[name])
+
+
+@pytest.mark.parametrize("name", ["tiny", "llama_small"])
+def test_recompute_is_bit_identical(name):
+    w = SI.WORKLOADS[name] if name in SI.WORKLOADS else REDUCED[name]
+    outs = []
+    for rc in (0, 1):
+        st, ys, dxs = _run_case(w, recompute=rc)
+        outs.append((ys, dxs, st.grads.clone()))
+    for a, b in zip(outs[0][0] + outs[0][1], outs[1][0] + outs[1][1]):
+        assert np.array_equal(a, b)
+    assert torch.equal(outs[0][2], outs[1][2])
+
+
+def test_deterministic_and_slot_independent():
+    """Same inputs twice -> same bits; an interleaved 1F1B pattern over 3 slots -> same bits."""
+    w = SI.WORKLOADS["tiny"]
+    gcfg, _ = U.make_cfgs(w, max_in_flight=3)
+    params, xs, dys = _inputs(dict(w, n_mb=4), 4)
+    st = P.Stage(gcfg)
+    U.load_params(st, params)
+    ys1, dxs1 = U.run_gpu(st, xs, dys)
+    g1 = st.grads.clone()
+    ys2, dxs2 = U.run_gpu(st, xs, dys)
+    assert all(np.array_equal(a, b) for a, b in zip(ys1 + dxs1, ys2 + dxs2))
+    assert torch.equal(g1, st.grads)
+    # warm-up F0 F1 F2, steady B0 F3 B1, drain B2 B3 (slot = micro-batch % 3)
+    xd = [U.to_dev(x) for x in xs]
+    dyd = [U.to_dev(d) for d in dys]
+    y = [torch.empty_like(t) for t in xd]
+    dx = [torch.empty_like(t) for t in xd]
+    st.zero_grads()
+    for m in (0, 1, 2):
+        st.forward(m % 3, xd[m], y[m])
+    st.backward(0, dyd[0], dx[0])
+    st.forward(0, xd[3], y[3])
+    st.backward(1, dyd[1], dx[1])
+    st.backward(2, dyd[2], dx[2])
+    st.backward(0, dyd[3], dx[3])
+    torch.cuda.synchronize()
+    assert all(np.array_equal(U.to_np(a), b) for a, b in zip(y + dx, ys1 + dxs1))
+    assert torch.equal(g1, st.grads)
+
+
+def test_causality_is_bit_exact_on_gpu():
+    w = SI.WORKLOADS["tiny"]
+    gcfg, _ = U.make_cfgs(w)
+    params, xs, _ = _inputs(w, 1)
+    st = P.Stage(gcfg)
+    U.load_params(st, params)
+    B, S, t = w["mb"], w["seq"], 70
+    x = xs[0].reshape(B, S, -1).copy()
+    x2 = x.copy()
+    x2[:, t + 1:] = SI.round_bf16(x2[:, t + 1:] * 0.5 + 0.25)
+    outs = []
+    for a in (x, x2):
+        xd = U.to_dev(a.reshape(B * S, -1))
+        y = torch.empty_like(xd)
+        st.forward(0, xd, y)
+        dx = torch.empty_like(xd)
+        st.backward(0, xd, dx)
+        torch.cuda.synchronize()
+        outs.append(U.to_np(y).reshape(B, S, -1))
+    assert np.array_equal(outs[0][:, : t + 1], outs[1][:, : t + 1])
+    assert not np.array_equal(outs[0][:, t + 1:], outs[1][:, t + 1:])
+
+
+def test_state_errors():
+    w = SI.WORKLOADS["tiny"]
+    gcfg, _ = U.make_cfgs(w)
+    st = P.Stage(gcfg)
+    x = torch.zeros(w["mb"] * w["seq"], w["hidden"], dtype=torch.bfloat16, device="cuda")
+    y = torch.empty_like(x)
+    with pytest.raises(P.AhError) as e:
+        st.backward(0, x, y)
+    assert e.value.status == 3
+    st.forward(0, x, y)
+    with pytest.raises(P.AhError) as e:
+        st.forward(0, x, y)
+    assert e.value.status == 3
+    with pytest.raises(P.AhError) as e:
+        st.forward(1, x, y)
+    assert e.value.status == 1
+    st.backward(0, x, y)
+    torch.cuda.synchronize()
+
+
+def test_profile_reports_layers_and_bytes():
+    w = dict(SI.WORKLOADS["tiny"], n_layers=3)
+    gcfg, _ = U.make_cfgs(w, max_in_flight=2)
+    st = P.Stage(gcfg)
+    st.params.normal_(0, 0.02)
+    prof = st.profile(warmup=1, iters=3)
+    assert len(prof["fwd_ms"]) == 3 and all(t > 0 for t in prof["fwd_ms"] + prof["bwd_ms"])
+    assert abs(sum(prof["fwd_ms"]) - prof["stage_fwd_ms"]) <= 0.25 * prof["stage_fwd_ms"] + 0.05
+    assert prof["peak_activation_bytes"] == 2 * st.sizes["activation_bytes_per_slot"] + st.sizes["workspace_bytes"]
+    assert prof["activation_bytes_per_layer_per_slot"] * 3 == st.sizes["activation_bytes_per_slot"]
+    assert prof["param_bytes"] == st.sizes["param_bytes"] and prof["grad_bytes"] == 2 * prof["param_bytes"]
+    assert prof["iteration_ms"] > 0
