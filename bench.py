@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Throughput of one pipeline stage on one MI355X.
+
+A step is one training iteration of the stage: K micro-batches, each a forward
+and a backward pass through all layers, gradients accumulated in fp32 (restarted
+at micro-batch 0).  Workload: the 7B-class TP=2 shard (4 layers, hidden 4096,
+16 local heads x 128, local FFN 8192, seq 2048, micro-batch 2, K = 8), synthetic
+seeded data already resident in HBM.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def model_flops_per_iter(w):
+    """2 flop per MAC, causal attention at its real half cost, backward = 2 x forward, recompute not counted."""
+    tp = w["tp"]
+    h, hl, F = w["hidden"], w["n_heads"] // tp * w["head_dim"], w["ffn"] // tp
+    S = w["seq"]
+    mlp = (6 if w["arch"] == "llama" else 4) * h * F
+    per_token_layer = 2 * h * 3 * hl + 2 * hl * h + mlp + 4 * hl * (S + 1) / 2
+    return 3.0 * per_token_layer * w["n_layers"] * w["mb"] * S * w["n_mb"]
+
+
+def cpu_baseline(w, name):
+    """The oracle as it stands, float32, on a bounded sample: one layer, one sequence, forward + backward."""
+    import numpy as np
+    from oracle import stage_ref as R
+    from synth import stage_inputs as SI
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+    except Exception:
+        cores = os.cpu_count()
+    ws = dict(w, n_layers=1, mb=1)
+    nh, hl, Fl = SI.local_dims(ws)
+    cfg = R.StageCfg(ws["arch"], 1, ws["hidden"], nh, ws["head_dim"], Fl, ws["seq"], 1e-5 if ws["arch"] == "gpt" else 1e-6)
+    rng = np.random.default_rng(0)
+    params = [{n: (np.ones(s, np.float32) if k == "one" else np.zeros(s, np.float32) if k == "zero"
+                   else (rng.standard_normal(s, dtype=np.float32) * np.float32(0.02)))
+               for n, s, k in SI.param_spec(ws["arch"], ws["hidden"], hl, Fl)}]
+    x = rng.standard_normal((ws["seq"], ws["hidden"]), dtype=np.float32)
+    dy = rng.standard_normal((ws["seq"], ws["hidden"]), dtype=np.float32)
+    grads = R.zero_grads_like(params)
+    t0 = time.perf_counter()
+    y, caches, _ = R.stage_fwd(cfg, params, x)
+    R.stage_bwd(cfg, params, caches, dy, grads)
+    dt = time.perf_counter() - t0
+    return {"value": ws["seq"] / (dt * w["n_layers"]), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "workload %s: 1 of %d layers, 1 sequence of %d tokens, forward+backward in float32 numpy, %.1f s; "
+                      "tokens/s = %d / (%d layers x that time)" % (name, w["n_layers"], ws["seq"], dt, ws["seq"], w["n_layers"])}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gpt7b_tp2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--trace-steps", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's stage; this build has no multi-GPU path (--gpus %d refused)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_20953_amd as P
+    from synth import stage_inputs as SI
+
+    w = SI.WORKLOADS[args.workload]
+    torch.manual_seed(SI.BASE_SEED)
+    dev = torch.device("cuda:0")
+    cfg = P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
+                             head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
+                             max_in_flight=1, recompute=w["recompute"])
+    st = P.Stage(cfg, device=dev)
+    # synthetic weights of the stated distribution, generated on the device: N(0, 0.02), gains 1, biases 0
+    st.params.normal_(0.0, 0.02)
+    for l in range(w["n_layers"]):
+        for name in (["ln1_g", "ln2_g"]):
+            st.param_view(l, name).fill_(1.0)
+        if w["arch"] == "gpt":
+            for name in ("ln1_b", "ln2_b", "bqkv", "bo", "b1", "b2"):
+                st.param_view(l, name).zero_()
+    T, K = w["mb"] * w["seq"], w["n_mb"]
+    xs = [torch.randn(T, w["hidden"], device=dev).to(torch.bfloat16) for _ in range(K)]
+    dys = [torch.randn(T, w["hidden"], device=dev).to(torch.bfloat16) for _ in range(K)]
+    y, dx = torch.empty_like(xs[0]), torch.empty_like(xs[0])
+    stream = torch.cuda.current_stream()
+
+    def step():
+        st.zero_grads(stream)
+        for m in range(K):
+            st.forward(0, xs[m], y, stream)
+            st.backward(0, dys[m], dx, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    assert torch.isfinite(st.grads).all() and torch.isfinite(dx.float()).all()
+    tokens = T * K
+    flops = model_flops_per_iter(w)
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-call-site durations, measured with HIP event pairs on the launch stream over the same steps
+    st.trace_begin()
+    for _ in range(max(1, args.trace_steps)):
+        step()
+    sites = st.trace_end()
+    for s in sites:
+        avg = s["total_ms"] / s["launches"]
+        s["avg_us"] = avg * 1e3
+        if s["flops_per_launch"] > 0:
+            s["tflops"] = s["flops_per_launch"] / (avg * 1e-3) / 1e12
+        elif s["bytes_per_launch"] > 0:
+            s["gbs"] = s["bytes_per_launch"] / (avg * 1e-3) / 1e9
+    mfma_sites = [s for s in sites if s["flops_per_launch"] > 0]
+    dom = max(mfma_sites, key=lambda s: s["total_ms"])
+    roofline = {"bound": "mfma", "kernel": dom["name"], "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": dom["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
+                "avg_launch_us": dom["avg_us"], "launches": dom["launches"], "flops_per_launch": dom["flops_per_launch"]}
+
+    out = {"metric": "stage fwd+bwd tokens/s and TFLOP/s (% bf16 MFMA peak) at 1 MI355X",
+           "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic", "model_tflops": tflops, "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+           "wall_ms_per_step": wall * 1e3 / args.steps,
+           "config": {"workload": args.workload, "arch": w["arch"], "layers": w["n_layers"], "hidden": w["hidden"],
+                      "local_heads": w["n_heads"] // w["tp"], "head_dim": w["head_dim"], "local_ffn": w["ffn"] // w["tp"],
+                      "seq_len": w["seq"], "microbatch": w["mb"], "microbatches": K, "tokens_per_step": tokens,
+                      "tp_degree": w["tp"], "recompute": w["recompute"], "parallelism": "1 GPU (one TP shard of one stage)"},
+           "roofline": roofline,
+           "sites": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in s.items()} for s in sites]}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -158,6 +158,21 @@ int ah_stage_zero_grads(ah_stage_t* st, void* hip_stream);
  * overwrites the gradient buffer, and synchronises the device. */
 int ah_stage_profile(ah_stage_t* st, int warmup, int iters, ah_stage_profile_t* out);
 
+/* Per-call-site timing of the kernels that forward / backward enqueue, for the
+ * roofline report (Section III-D's profiler only needs whole-layer times; this
+ * is the finer view).  Between _begin and _end every launch site is bracketed
+ * by a HIP event pair on the stream it is launched on; _end synchronises the
+ * device and fills up to `capacity` entries, one per site that ran. */
+typedef struct {
+  char name[32];            /* e.g. "gemm_nn.fc1_fwd", "attention_bwd", "norm_fwd" */
+  int64_t launches;         /* event pairs recorded for this site */
+  double total_ms;          /* sum of their durations */
+  double flops_per_launch;  /* algorithmic flops of one launch (0 for bandwidth-bound sites) */
+  double bytes_per_launch;  /* algorithmic HBM bytes of one launch (0 for the MFMA-bound sites) */
+} ah_trace_entry_t;
+int ah_stage_trace_begin(ah_stage_t* st);
+int ah_stage_trace_end(ah_stage_t* st, ah_trace_entry_t* out, int capacity, int* n_out);
+
 /* Message for the calling thread's last non-OK status (never NULL). */
 const char* ah_last_error(void);
 

@@ -1,8 +1,15 @@
 """MI355X-native pipeline-stage compute (forward + backward of a run of decoder
 layers on one tensor-parallel shard).  Thin ctypes binding over libahstage.so;
 every step runs in the HIP kernels of that library."""
-from .binding import (AH_ARCH_GPT, AH_ARCH_LLAMA, PARAM_INDEX, AhError, Stage, StageConfig, attention_bwd, attention_fwd,
-                      gemm_nn, gemm_nt, gemm_tn, lib, library_path)
+import importlib
 
-__all__ = ["AH_ARCH_GPT", "AH_ARCH_LLAMA", "PARAM_INDEX", "AhError", "Stage", "StageConfig", "attention_bwd",
-           "attention_fwd", "gemm_nn", "gemm_nt", "gemm_tn", "lib", "library_path"]
+_LAZY = ("AH_ARCH_GPT", "AH_ARCH_LLAMA", "PARAM_INDEX", "AhError", "Stage", "StageConfig", "attention_bwd",
+         "attention_fwd", "gemm_nn", "gemm_nt", "gemm_tn", "lib", "library_path", "query_sizes")
+
+
+def __getattr__(name):
+    # the binding loads libahstage.so on first use, so that importing the package
+    # (to reach paper_2512_20953_amd.build) works before the library is built
+    if name in _LAZY:
+        return getattr(importlib.import_module(__name__ + ".binding"), name)
+    raise AttributeError(name)

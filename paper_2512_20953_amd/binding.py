@@ -53,6 +53,11 @@ class _Profile(C.Structure):
                 ("activation_bytes_per_layer_per_slot", C.c_uint64), ("param_bytes", C.c_uint64), ("grad_bytes", C.c_uint64)]
 
 
+class _TraceEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("launches", C.c_int64), ("total_ms", C.c_double),
+                ("flops_per_launch", C.c_double), ("bytes_per_launch", C.c_double)]
+
+
 def library_path():
     return os.path.join(HERE, "libahstage.so")
 
@@ -74,6 +79,8 @@ def _load():
     L.ah_stage_grads.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_uint64)]
     L.ah_stage_zero_grads.argtypes = [vp, vp]
     L.ah_stage_profile.argtypes = [vp, i, i, C.POINTER(_Profile)]
+    L.ah_stage_trace_begin.argtypes = [vp]
+    L.ah_stage_trace_end.argtypes = [vp, C.POINTER(_TraceEntry), i, C.POINTER(i)]
     L.ah_gemm_nn.argtypes = [vp, vp, vp, vp, i, i, i, vp]
     L.ah_gemm_nt.argtypes = [vp, vp, vp, i, i, i, vp]
     L.ah_gemm_tn.argtypes = [vp, vp, vp, i, i, i, i, vp]
@@ -161,6 +168,17 @@ class Stage:
         p, n = C.c_void_p(), C.c_uint64()
         _check(lib.ah_stage_grads(self._h, C.byref(p), C.byref(n)))
         return p.value, n.value
+
+    def trace_begin(self):
+        _check(lib.ah_stage_trace_begin(self._h))
+
+    def trace_end(self):
+        arr = (_TraceEntry * 32)()
+        n = C.c_int()
+        _check(lib.ah_stage_trace_end(self._h, arr, 32, C.byref(n)))
+        return [{"name": arr[k].name.decode(), "launches": int(arr[k].launches), "total_ms": arr[k].total_ms,
+                 "flops_per_launch": arr[k].flops_per_launch, "bytes_per_launch": arr[k].bytes_per_launch}
+                for k in range(n.value)]
 
     def profile(self, warmup=2, iters=5):
         L = self.cfg.n_layers

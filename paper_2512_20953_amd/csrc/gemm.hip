@@ -45,10 +45,10 @@ __device__ __forceinline__ uint32_t loader_src_offset(int chunk, int lane, int l
   }
 }
 
-template <int W, bool KS>
+template <int W, bool KS, int NW>
 __device__ __forceinline__ void issue_tile_loads(const bf16* __restrict__ g, const uint32_t* off, char* __restrict__ lds, int wave) {
 #pragma unroll
-  for (int i = 0; i < W / 32; i++) load16_to_lds(g + off[i], lds + (wave + 4 * i) * 1024);
+  for (int i = 0; i < W / 8 / NW; i++) load16_to_lds(g + off[i], lds + (wave + NW * i) * 1024);
 }
 
 // fragment (8 k-values for row/col = lane % 32 of a 32-wide block) for k-step ks
@@ -70,49 +70,96 @@ __device__ __forceinline__ bf16x8 read_frag(const char* __restrict__ lds, int ba
   }
 }
 
-template <int BM, int BN, bool AKS, bool BKS>
-__device__ __forceinline__ void mma_stage(const char* __restrict__ cA, const char* __restrict__ cB,
-                                          f32x16 (&acc)[BM / 64][BN / 64], int wm, int wn, int lane) {
-  constexpr int TM = BM / 64, TN = BN / 64;
+// Fragments of one 16-wide k-step for the wave's sub-tile.
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+struct Frags {
+  static constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+  bf16x8 a[TM], b[TN];
+  __device__ __forceinline__ void load(const char* __restrict__ cA, const char* __restrict__ cB, int ks, int wm, int wn, int lane) {
 #pragma unroll
-  for (int ks = 0; ks < 4; ks++) {
-    bf16x8 af[TM], bfr[TN];
+    for (int t = 0; t < TM; t++) a[t] = read_frag<BM, AKS>(cA, wm * (BM / WGM), t, ks, lane);
 #pragma unroll
-    for (int t = 0; t < TM; t++) af[t] = read_frag<BM, AKS>(cA, wm * (BM / 2), t, ks, lane);
+    for (int t = 0; t < TN; t++) b[t] = read_frag<BN, BKS>(cB, wn * (BN / WGN), t, ks, lane);
+  }
+};
+
+// Scheduling hint: spread the NR LDS reads issued for the next k-step between the
+// NM MFMAs of the current one (masks: 0x100 = LDS read, 0x008 = MFMA).
+template <int NR, int NM>
+__device__ __forceinline__ void interleave_reads_with_mfma() {
+  if constexpr (NR >= NM) {
 #pragma unroll
-    for (int t = 0; t < TN; t++) bfr[t] = read_frag<BN, BKS>(cB, wn * (BN / 2), t, ks, lane);
+    for (int i = 0; i < NM; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NR / NM, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
+  } else {
 #pragma unroll
-    for (int tm = 0; tm < TM; tm++)
-#pragma unroll
-      for (int tn = 0; tn < TN; tn++)
-        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tm][tn], 0, 0, 0);
+    for (int i = 0; i < NR; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, NM / NR, 0);
+    }
   }
 }
 
-// One pipeline step: start the loads of the next k-tile into (nA, nB) and
-// multiply the current one from (cA, cB).  The restrict qualifiers tell the
-// compiler that the LDS reads of this step never touch the buffers being filled.
-template <int BM, int BN, bool AKS, bool BKS>
-__device__ __forceinline__ void pipe_step(bool prefetch, const bf16* gA, const bf16* gB, const uint32_t* offA, const uint32_t* offB,
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+__device__ __forceinline__ void mma_step(const Frags<BM, BN, WGM, WGN, AKS, BKS>& f, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+#pragma unroll
+  for (int tm = 0; tm < TM; tm++)
+#pragma unroll
+    for (int tn = 0; tn < TN; tn++)
+      acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[tn], f.a[tm], acc[tm][tn], 0, 0, 0);
+}
+
+// One k-tile of the pipeline.  On entry f0 holds the fragments of k-step 0 of
+// (cA, cB).  Starts the loads of the next k-tile into (nA, nB), multiplies the
+// current one while the fragments of each following k-step are fetched, and
+// before the last k-step waits for the next tile (its own loads, then the
+// block barrier) so that f0 can be refilled from (nA, nB) under the last MFMAs.
+// The restrict qualifiers tell the compiler that LDS reads of (cA, cB) never
+// touch the buffers being filled.
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+__device__ __forceinline__ void pipe_step(bool prefetch, int dbg, const bf16* gA, const bf16* gB, const uint32_t* offA, const uint32_t* offB,
                                           char* __restrict__ nA, char* __restrict__ nB, const char* __restrict__ cA,
-                                          const char* __restrict__ cB, f32x16 (&acc)[BM / 64][BN / 64], int wave, int wm, int wn, int lane) {
+                                          const char* __restrict__ cB, Frags<BM, BN, WGM, WGN, AKS, BKS>& f0,
+                                          Frags<BM, BN, WGM, WGN, AKS, BKS>& f1, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32],
+                                          int wave, int wm, int wn, int lane) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+  constexpr int NR = TM * (AKS ? 2 : 1) + TN * (BKS ? 2 : 1), NM = TM * TN;
   if (prefetch) {
-    issue_tile_loads<BM, AKS>(gA, offA, nA, wave);
-    issue_tile_loads<BN, BKS>(gB, offB, nB, wave);
+    issue_tile_loads<BM, AKS, WGM * WGN>(gA, offA, nA, wave);
+    issue_tile_loads<BN, BKS, WGM * WGN>(gB, offB, nB, wave);
   }
-  mma_stage<BM, BN, AKS, BKS>(cA, cB, acc, wm, wn, lane);
+  if (dbg < 3) f1.load(cA, cB, 1, wm, wn, lane);
+  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
+  interleave_reads_with_mfma<NR, NM>();
+  if (dbg < 3) f0.load(cA, cB, 2, wm, wn, lane);
+  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
+  interleave_reads_with_mfma<NR, NM>();
+  if (dbg < 3) f1.load(cA, cB, 3, wm, wn, lane);
+  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
+  interleave_reads_with_mfma<NR, NM>();
+  if (dbg < 2) {
+    __builtin_amdgcn_s_waitcnt(0);  // own loads of the next tile have landed, own reads of this one are done
+    __syncthreads();
+  }
+  if (dbg < 3) f0.load(nA, nB, 0, wm, wn, lane);
+  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
+  interleave_reads_with_mfma<NR, NM>();
 }
 
-template <int BM, int BN, bool AKS, bool BKS, int EPI>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
-  constexpr int TM = BM / 64, TN = BN / 64;
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
   __shared__ __attribute__((aligned(1024))) char sA0[BM * 128];
   __shared__ __attribute__((aligned(1024))) char sA1[BM * 128];
   __shared__ __attribute__((aligned(1024))) char sB0[BN * 128];
   __shared__ __attribute__((aligned(1024))) char sB1[BN * 128];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in scalar registers
+  const int wm = wave / WGN, wn = wave % WGN;
 
   // block -> tile: consecutive logical tiles share an XCD (blocks are dealt to the
   // 8 XCDs round-robin), and run down groups of 8 tile-rows so that the tiles in
@@ -134,11 +181,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   const size_t stepA = AKS ? (size_t)BK * g.lda : (size_t)BK;
   const size_t stepB = BKS ? (size_t)BK * g.ldb : (size_t)BK;
 
-  uint32_t offA[BM / 32], offB[BN / 32];
+  uint32_t offA[BM / 8 / NW], offB[BN / 8 / NW];
 #pragma unroll
-  for (int i = 0; i < BM / 32; i++) offA[i] = loader_src_offset<BM, AKS>(wave + 4 * i, lane, g.lda);
+  for (int i = 0; i < BM / 8 / NW; i++) offA[i] = loader_src_offset<BM, AKS>(wave + NW * i, lane, g.lda);
 #pragma unroll
-  for (int i = 0; i < BN / 32; i++) offB[i] = loader_src_offset<BN, BKS>(wave + 4 * i, lane, g.ldb);
+  for (int i = 0; i < BN / 8 / NW; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -149,23 +196,22 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
   const int nk = g.K / BK;
-  issue_tile_loads<BM, AKS>(gA, offA, sA0, wave);
-  issue_tile_loads<BN, BKS>(gB, offB, sB0, wave);
+  issue_tile_loads<BM, AKS, NW>(gA, offA, sA0, wave);
+  issue_tile_loads<BN, BKS, NW>(gB, offB, sB0, wave);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
+  Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
+  f0.load(sA0, sB0, 0, wm, wn, lane);
   // nk is even (K is a multiple of 128): two k-tiles per trip, buffers alternate
   for (int kt = 0; kt < nk; kt += 2) {
     gA += stepA;
     gB += stepB;
-    pipe_step<BM, BN, AKS, BKS>(true, gA, gB, offA, offB, sA1, sB1, sA0, sB0, acc, wave, wm, wn, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+    pipe_step<BM, BN, WGM, WGN, AKS, BKS>(!g.debug_noload, g.debug_noload, gA, gB, offA, offB, sA1, sB1, sA0, sB0, f0, f1, acc, wave, wm, wn, lane);
     gA += stepA;
     gB += stepB;
-    pipe_step<BM, BN, AKS, BKS>(kt + 2 < nk, gA, gB, offA, offB, sA0, sB0, sA1, sB1, acc, wave, wm, wn, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+    pipe_step<BM, BN, WGM, WGN, AKS, BKS>(!g.debug_noload && kt + 2 < nk, g.debug_noload, gA, gB, offA, offB, sA0, sB0, sA1, sB1, f0, f1, acc, wave,
+                                          wm, wn, lane);
   }
 
   // ---- epilogue: lane holds C[m][n .. n+3] for 4 column groups of each 32x32 block
@@ -176,7 +222,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   for (int tn = 0; tn < TN; tn++) {
 #pragma unroll
     for (int q = 0; q < 4; q++) {
-      const int n = n0 + wn * (BN / 2) + tn * 32 + 8 * q + 4 * (lane >> 5);
+      const int n = n0 + wn * (BN / WGN) + tn * 32 + 8 * q + 4 * (lane >> 5);
       float bv[4] = {0.f, 0.f, 0.f, 0.f};
       if (has_bias) {
         bf16x4 b = *(const bf16x4*)(bias + n);
@@ -185,7 +231,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
       }
 #pragma unroll
       for (int tm = 0; tm < TM; tm++) {
-        const int m = m0 + wm * (BM / 2) + tm * 32 + (lane & 31);
+        const int m = m0 + wm * (BM / WGM) + tm * 32 + (lane & 31);
         float v[4];
 #pragma unroll
         for (int i = 0; i < 4; i++) v[i] = acc[tm][tn][4 * q + i] + bv[i];
@@ -230,8 +276,11 @@ namespace {
 // Tile choice: the 256-CU chip runs one block per CU, so a launch costs
 // ceil(tiles / 256) rounds of one tile's time.  Relative tile costs (per output
 // element) are measured constants: smaller tiles re-read more from LDS and L2.
-struct TileCfg { int bm, bn; float cost; };
-const TileCfg kTiles[] = {{256, 256, 1.00f}, {256, 128, 1.12f}, {128, 256, 1.12f}, {128, 128, 1.35f}};
+struct TileCfg { int bm, bn, wgm, wgn; float cost; };
+const TileCfg kTiles[] = {{256, 256, 2, 2, 1.00f}, {256, 128, 2, 2, 1.12f}, {128, 256, 2, 2, 1.12f}, {128, 128, 2, 2, 1.35f},
+                          {256, 256, 2, 4, 1.00f}, {256, 256, 4, 2, 1.00f}, {256, 128, 4, 2, 1.12f}, {128, 256, 2, 4, 1.12f}};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+constexpr int kAutoTiles = 4;  // the automatic choice looks at the first kAutoTiles entries
 
 int pick_tile(int M, int N) {
   static int forced = -2;
@@ -239,10 +288,10 @@ int pick_tile(int M, int N) {
     const char* e = getenv("AH_GEMM_TILE");  // tuning aid: index into kTiles
     forced = e ? atoi(e) : -1;
   }
-  if (forced >= 0 && forced < 4 && M % kTiles[forced].bm == 0 && N % kTiles[forced].bn == 0) return forced;
+  if (forced >= 0 && forced < kNumTiles && M % kTiles[forced].bm == 0 && N % kTiles[forced].bn == 0) return forced;
   int best = -1;
   float best_t = 0;
-  for (int i = 0; i < 4; i++) {
+  for (int i = 0; i < kAutoTiles; i++) {
     if (M % kTiles[i].bm || N % kTiles[i].bn) continue;
     long tiles = (long)(M / kTiles[i].bm) * (N / kTiles[i].bn);
     long rounds = (tiles + 255) / 256;
@@ -252,26 +301,34 @@ int pick_tile(int M, int N) {
   return best;
 }
 
-template <int BM, int BN, bool AKS, bool BKS, int EPI>
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS, int EPI>
 hipError_t run(const GemmArgs& a, hipStream_t s) {
   dim3 grid((a.M / BM) * (a.N / BN));
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, AKS, BKS, EPI>), grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, AKS, BKS, EPI>), grid, dim3(64 * WGM * WGN), 0, s, a);
   return hipGetLastError();
 }
 
 template <bool AKS, bool BKS, int EPI>
 hipError_t run_tile(int t, const GemmArgs& a, hipStream_t s) {
   switch (t) {
-    case 0: return run<256, 256, AKS, BKS, EPI>(a, s);
-    case 1: return run<256, 128, AKS, BKS, EPI>(a, s);
-    case 2: return run<128, 256, AKS, BKS, EPI>(a, s);
-    default: return run<128, 128, AKS, BKS, EPI>(a, s);
+    case 0: return run<256, 256, 2, 2, AKS, BKS, EPI>(a, s);
+    case 1: return run<256, 128, 2, 2, AKS, BKS, EPI>(a, s);
+    case 2: return run<128, 256, 2, 2, AKS, BKS, EPI>(a, s);
+    case 3: return run<128, 128, 2, 2, AKS, BKS, EPI>(a, s);
+    case 4: return run<256, 256, 2, 4, AKS, BKS, EPI>(a, s);
+    case 5: return run<256, 256, 4, 2, AKS, BKS, EPI>(a, s);
+    case 6: return run<256, 128, 4, 2, AKS, BKS, EPI>(a, s);
+    default: return run<128, 256, 2, 4, AKS, BKS, EPI>(a, s);
   }
 }
 
 }  // namespace
 
-hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
+hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in, hipStream_t s) {
+  GemmArgs a = a_in;
+  static int dbg = -1;
+  if (dbg < 0) dbg = getenv("AH_GEMM_NOLOAD") ? atoi(getenv("AH_GEMM_NOLOAD")) : 0;
+  a.debug_noload = dbg;
   if (!gemm_shape_ok(a.M, a.N, a.K)) return hipErrorInvalidValue;
   const int t = pick_tile(a.M, a.N);
   if (t < 0) return hipErrorInvalidValue;

@@ -24,6 +24,7 @@ struct GemmArgs {
   int lda, ldb, ldc, ld_aux;
   int M, N, K;
   int beta;
+  int debug_noload;  // timing experiment only: skip the main-loop loads (results are garbage)
 };
 
 // M, N, K multiples of 128, all leading dimensions multiples of 8.

@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -45,6 +46,11 @@ struct ah_stage {
   std::vector<char> busy;
   bool overwrite_grads;  // next backward writes instead of adding
   bool rope_ready;
+  // optional per-call-site timing (ah_stage_trace_begin / _end)
+  bool tracing;
+  std::vector<hipEvent_t> ev_pool;           // pairs, in launch order
+  std::vector<int> ev_site;                  // site of pair i
+  size_t ev_used;
 };
 
 namespace {
@@ -167,6 +173,43 @@ __global__ void fill_pattern_kernel(__bf16* p, size_t n, uint32_t seed) {
   p[i] = (__bf16)(((x & 0xffff) / 65536.0f - 0.5f) * 3.4641f);  // uniform, unit variance
 }
 
+// call sites that the trace distinguishes
+enum Site {
+  SITE_QKV_FWD, SITE_WO_FWD, SITE_FC1_FWD, SITE_FC2_FWD, SITE_FC2_WGRAD, SITE_FC2_DGRAD, SITE_FC1_WGRAD, SITE_FC1_DGRAD,
+  SITE_WO_WGRAD, SITE_WO_DGRAD, SITE_QKV_WGRAD, SITE_QKV_DGRAD, SITE_ATTN_FWD, SITE_ATTN_BWD, SITE_NORM_FWD, SITE_NORM_BWD,
+  SITE_COLSUM, SITE_ROPE, SITE_SWIGLU_FWD, SITE_SWIGLU_BWD, SITE_COUNT
+};
+const char* const kSiteNames[SITE_COUNT] = {
+  "gemm_nn.qkv_fwd", "gemm_nn.wo_fwd", "gemm_nn.fc1_fwd", "gemm_nn.fc2_fwd", "gemm_tn.fc2_wgrad", "gemm_nt.fc2_dgrad",
+  "gemm_tn.fc1_wgrad", "gemm_nt.fc1_dgrad", "gemm_tn.wo_wgrad", "gemm_nt.wo_dgrad", "gemm_tn.qkv_wgrad", "gemm_nt.qkv_dgrad",
+  "attention_fwd", "attention_bwd", "norm_fwd", "norm_bwd", "colsum", "rope", "swiglu_fwd", "swiglu_bwd"};
+
+// brackets the launches issued while it lives with an event pair when tracing
+struct SiteTimer {
+  ah_stage* s;
+  hipStream_t st;
+  size_t slot;
+  SiteTimer(ah_stage* s_, int site, hipStream_t st_) : s(s_), st(st_), slot((size_t)-1) {
+    if (!s->tracing) return;
+    if (s->ev_used + 2 > s->ev_pool.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess) return;
+      if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+      s->ev_pool.push_back(a);
+      s->ev_pool.push_back(b);
+      s->ev_site.push_back(site);
+    } else {
+      s->ev_site[s->ev_used / 2] = site;
+    }
+    slot = s->ev_used;
+    s->ev_used += 2;
+    (void)hipEventRecord(s->ev_pool[slot], st);
+  }
+  ~SiteTimer() {
+    if (slot != (size_t)-1) (void)hipEventRecord(s->ev_pool[slot + 1], st);
+  }
+};
+
 struct LayerPtrs {
   const char *ln1_g, *ln1_b, *wqkv, *bqkv, *wo, *bo, *ln2_g, *ln2_b, *w1, *b1, *w2, *b2;
   float *g_ln1_g, *g_ln1_b, *g_wqkv, *g_bqkv, *g_wo, *g_bo, *g_ln2_g, *g_ln2_b, *g_w1, *g_b1, *g_w2, *g_b2;
@@ -202,17 +245,25 @@ ActPtrs act_ptrs(const ah_stage* s, int slot, int layer) {
   return p;
 }
 
+#define TIMED(site, expr)                \
+  do {                                   \
+    SiteTimer t_(s, site, st);           \
+    hipError_t e_ = (expr);              \
+    if (e_ != hipSuccess) return e_;     \
+  } while (0)
+
 #define TRY(expr)                        \
   do {                                   \
     hipError_t e_ = (expr);              \
     if (e_ != hipSuccess) return e_;     \
   } while (0)
 
-hipError_t gemm(GemmLayout lay, GemmEpilogue epi, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N,
+hipError_t gemm(ah_stage* s, int site, GemmLayout lay, GemmEpilogue epi, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N,
                 int K, const void* bias, const void* aux, int ld_aux, void* C2, int beta, hipStream_t st) {
   GemmArgs g = {};
   g.A = A; g.B = B; g.C = C; g.C2 = C2; g.bias = bias; g.aux = aux;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ld_aux = ld_aux; g.M = M; g.N = N; g.K = K; g.beta = beta;
+  SiteTimer t(s, site, st);
   return launch_gemm(lay, epi, g, st);
 }
 
@@ -221,19 +272,19 @@ hipError_t gemm(GemmLayout lay, GemmEpilogue epi, const void* A, int lda, const 
 hipError_t layer_forward(ah_stage* s, int layer, const ActPtrs& a, void* y, hipStream_t st) {
   const LayerPtrs p = layer_ptrs(s, layer);
   const int T = s->T, h = s->h, hl = s->hl, F = s->F, B = s->cfg.microbatch_size, S = s->cfg.seq_len;
-  TRY(launch_norm_fwd(s->llama, a.x_in, p.ln1_g, p.ln1_b, a.a, (float*)a.stats1, T, h, s->eps, st));
-  TRY(gemm(GEMM_NN, EPI_BF16, a.a, h, p.wqkv, 3 * hl, a.qkv, 3 * hl, T, 3 * hl, h, p.bqkv, nullptr, 0, nullptr, 0, st));
-  if (s->llama) TRY(launch_rope(a.qkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, 1.f, st));
-  TRY(launch_attention_fwd(a.qkv, a.o, (float*)a.lse, B, S, s->nh, s->d, st));
-  TRY(gemm(GEMM_NN, EPI_RESID, a.o, hl, p.wo, h, a.x_mid, h, T, h, hl, p.bo, a.x_in, h, nullptr, 0, st));
-  TRY(launch_norm_fwd(s->llama, a.x_mid, p.ln2_g, p.ln2_b, a.c, (float*)a.stats2, T, h, s->eps, st));
+  TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_in, p.ln1_g, p.ln1_b, a.a, (float*)a.stats1, T, h, s->eps, st));
+  TRY(gemm(s, SITE_QKV_FWD, GEMM_NN, EPI_BF16, a.a, h, p.wqkv, 3 * hl, a.qkv, 3 * hl, T, 3 * hl, h, p.bqkv, nullptr, 0, nullptr, 0, st));
+  if (s->llama) TIMED(SITE_ROPE, launch_rope(a.qkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, 1.f, st));
+  TIMED(SITE_ATTN_FWD, launch_attention_fwd(a.qkv, a.o, (float*)a.lse, B, S, s->nh, s->d, st));
+  TRY(gemm(s, SITE_WO_FWD, GEMM_NN, EPI_RESID, a.o, hl, p.wo, h, a.x_mid, h, T, h, hl, p.bo, a.x_in, h, nullptr, 0, st));
+  TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_mid, p.ln2_g, p.ln2_b, a.c, (float*)a.stats2, T, h, s->eps, st));
   if (!s->llama) {
-    TRY(gemm(GEMM_NN, EPI_GELU, a.c, h, p.w1, F, a.u, F, T, F, h, p.b1, nullptr, 0, a.g, 0, st));
+    TRY(gemm(s, SITE_FC1_FWD, GEMM_NN, EPI_GELU, a.c, h, p.w1, F, a.u, F, T, F, h, p.b1, nullptr, 0, a.g, 0, st));
   } else {
-    TRY(gemm(GEMM_NN, EPI_BF16, a.c, h, p.w1, 2 * F, a.u, 2 * F, T, 2 * F, h, nullptr, nullptr, 0, nullptr, 0, st));
-    TRY(launch_swiglu_fwd(a.u, a.g, T, F, st));
+    TRY(gemm(s, SITE_FC1_FWD, GEMM_NN, EPI_BF16, a.c, h, p.w1, 2 * F, a.u, 2 * F, T, 2 * F, h, nullptr, nullptr, 0, nullptr, 0, st));
+    TIMED(SITE_SWIGLU_FWD, launch_swiglu_fwd(a.u, a.g, T, F, st));
   }
-  if (y) TRY(gemm(GEMM_NN, EPI_RESID, a.g, F, p.w2, h, y, h, T, h, F, p.b2, a.x_mid, h, nullptr, 0, st));
+  if (y) TRY(gemm(s, SITE_FC2_FWD, GEMM_NN, EPI_RESID, a.g, F, p.w2, h, y, h, T, h, F, p.b2, a.x_mid, h, nullptr, 0, st));
   return hipSuccess;
 }
 
@@ -248,44 +299,44 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   const bool rms = s->llama;
 
   // second MLP matrix: dW2 += g^T dy ; input gradient of the activation
-  TRY(gemm(GEMM_TN, EPI_F32_ACC, a.g, F, dy, h, p.g_w2, h, F, h, T, nullptr, nullptr, 0, nullptr, beta, st));
+  TRY(gemm(s, SITE_FC2_WGRAD, GEMM_TN, EPI_F32_ACC, a.g, F, dy, h, p.g_w2, h, F, h, T, nullptr, nullptr, 0, nullptr, beta, st));
   if (!s->llama) {
-    TRY(gemm(GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, dbig, F, T, F, h, nullptr, a.u, F, nullptr, 0, st));  // du
-    TRY(launch_colsum_partial(dbig, T, F, F, part, st));
-    TRY(launch_colsum_finish(part, cb, F, p.g_b1, beta, st));
-    TRY(gemm(GEMM_TN, EPI_F32_ACC, a.c, h, dbig, F, p.g_w1, F, h, F, T, nullptr, nullptr, 0, nullptr, beta, st));
-    TRY(gemm(GEMM_NT, EPI_BF16, dbig, F, p.w1, F, dsm, h, T, h, F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
+    TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, dbig, F, T, F, h, nullptr, a.u, F, nullptr, 0, st));  // du
+    TIMED(SITE_COLSUM, launch_colsum_partial(dbig, T, F, F, part, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish(part, cb, F, p.g_b1, beta, st));
+    TRY(gemm(s, SITE_FC1_WGRAD, GEMM_TN, EPI_F32_ACC, a.c, h, dbig, F, p.g_w1, F, h, F, T, nullptr, nullptr, 0, nullptr, beta, st));
+    TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, dbig, F, p.w1, F, dsm, h, T, h, F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
   } else {
-    TRY(gemm(GEMM_NT, EPI_BF16, dy, h, p.w2, h, dsm, F, T, F, h, nullptr, nullptr, 0, nullptr, 0, st));  // dm
-    TRY(launch_swiglu_bwd(dsm, a.u, dbig, T, F, st));                                                     // d(gate|up)
-    TRY(gemm(GEMM_TN, EPI_F32_ACC, a.c, h, dbig, 2 * F, p.g_w1, 2 * F, h, 2 * F, T, nullptr, nullptr, 0, nullptr, beta, st));
-    TRY(gemm(GEMM_NT, EPI_BF16, dbig, 2 * F, p.w1, 2 * F, dsm, h, T, h, 2 * F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
+    TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_BF16, dy, h, p.w2, h, dsm, F, T, F, h, nullptr, nullptr, 0, nullptr, 0, st));  // dm
+    TIMED(SITE_SWIGLU_BWD, launch_swiglu_bwd(dsm, a.u, dbig, T, F, st));                                                     // d(gate|up)
+    TRY(gemm(s, SITE_FC1_WGRAD, GEMM_TN, EPI_F32_ACC, a.c, h, dbig, 2 * F, p.g_w1, 2 * F, h, 2 * F, T, nullptr, nullptr, 0, nullptr, beta, st));
+    TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, dbig, 2 * F, p.w1, 2 * F, dsm, h, T, h, 2 * F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
   }
   // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
-  TRY(launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part, T, h, st));
-  TRY(launch_colsum_finish(part, nb, h, p.g_ln2_g, beta, st));
+  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part, T, h, st));
+  TIMED(SITE_COLSUM, launch_colsum_finish(part, nb, h, p.g_ln2_g, beta, st));
   if (!rms) {
-    TRY(launch_colsum_finish(part + (size_t)nb * h, nb, h, p.g_ln2_b, beta, st));
-    TRY(launch_colsum_finish(part + (size_t)2 * nb * h, nb, h, p.g_b2, beta, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish(part + (size_t)nb * h, nb, h, p.g_ln2_b, beta, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish(part + (size_t)2 * nb * h, nb, h, p.g_b2, beta, st));
   }
   // output projection
-  TRY(gemm(GEMM_TN, EPI_F32_ACC, a.o, hl, dmid, h, p.g_wo, h, hl, h, T, nullptr, nullptr, 0, nullptr, beta, st));
-  TRY(gemm(GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
+  TRY(gemm(s, SITE_WO_WGRAD, GEMM_TN, EPI_F32_ACC, a.o, hl, dmid, h, p.g_wo, h, hl, h, T, nullptr, nullptr, 0, nullptr, beta, st));
+  TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
   // attention
-  TRY(launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dbig, delta, B, S, s->nh, s->d, st));
-  if (s->llama) TRY(launch_rope(dbig, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
+  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dbig, delta, B, S, s->nh, s->d, st));
+  if (s->llama) TIMED(SITE_ROPE, launch_rope(dbig, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
   if (!s->llama) {
-    TRY(launch_colsum_partial(dbig, T, 3 * hl, 3 * hl, part, st));
-    TRY(launch_colsum_finish(part, cb, 3 * hl, p.g_bqkv, beta, st));
+    TIMED(SITE_COLSUM, launch_colsum_partial(dbig, T, 3 * hl, 3 * hl, part, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish(part, cb, 3 * hl, p.g_bqkv, beta, st));
   }
-  TRY(gemm(GEMM_TN, EPI_F32_ACC, a.a, h, dbig, 3 * hl, p.g_wqkv, 3 * hl, h, 3 * hl, T, nullptr, nullptr, 0, nullptr, beta, st));
-  TRY(gemm(GEMM_NT, EPI_BF16, dbig, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
+  TRY(gemm(s, SITE_QKV_WGRAD, GEMM_TN, EPI_F32_ACC, a.a, h, dbig, 3 * hl, p.g_wqkv, 3 * hl, h, 3 * hl, T, nullptr, nullptr, 0, nullptr, beta, st));
+  TRY(gemm(s, SITE_QKV_DGRAD, GEMM_NT, EPI_BF16, dbig, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
   // first norm backward; dx = dx_mid + norm_bwd(da); column sums give d(gain), d(offset), d(bo)
-  TRY(launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part, T, h, st));
-  TRY(launch_colsum_finish(part, nb, h, p.g_ln1_g, beta, st));
+  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part, T, h, st));
+  TIMED(SITE_COLSUM, launch_colsum_finish(part, nb, h, p.g_ln1_g, beta, st));
   if (!rms) {
-    TRY(launch_colsum_finish(part + (size_t)nb * h, nb, h, p.g_ln1_b, beta, st));
-    TRY(launch_colsum_finish(part + (size_t)2 * nb * h, nb, h, p.g_bo, beta, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish(part + (size_t)nb * h, nb, h, p.g_ln1_b, beta, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish(part + (size_t)2 * nb * h, nb, h, p.g_bo, beta, st));
   }
   return hipSuccess;
 }
@@ -368,11 +419,15 @@ extern "C" int ah_stage_create(const ah_stage_config_t* cfg, const ah_stage_buff
   s->busy.assign(cfg->max_in_flight, 0);
   s->overwrite_grads = true;
   s->rope_ready = false;
+  s->tracing = false;
+  s->ev_used = 0;
   *out = s;
   return AH_OK;
 }
 
 extern "C" int ah_stage_destroy(ah_stage_t* st) {
+  if (st)
+    for (hipEvent_t e : st->ev_pool) (void)hipEventDestroy(e);
   delete st;
   return AH_OK;
 }
@@ -485,6 +540,60 @@ extern "C" int ah_stage_profile(ah_stage_t* st, int warmup, int iters, ah_stage_
   out->activation_bytes_per_layer_per_slot = st->per_layer_slot_bytes;
   out->param_bytes = st->layer_elems * st->L * 2;
   out->grad_bytes = st->layer_elems * st->L * 4;
+  return AH_OK;
+}
+
+extern "C" int ah_stage_trace_begin(ah_stage_t* st) {
+  if (!st) return set_error(AH_EINVAL, "ah_stage_trace_begin: NULL argument");
+  st->tracing = true;
+  st->ev_used = 0;
+  return AH_OK;
+}
+
+extern "C" int ah_stage_trace_end(ah_stage_t* st, ah_trace_entry_t* out, int capacity, int* n_out) {
+  if (!st || !out || !n_out || capacity < 1) return set_error(AH_EINVAL, "ah_stage_trace_end: NULL argument or no capacity");
+  if (!st->tracing) return set_error(AH_ESTATE, "ah_stage_trace_end: no trace in progress");
+  st->tracing = false;
+  hipError_t e = hipDeviceSynchronize();
+  if (e != hipSuccess) return hip_status(e, "ah_stage_trace_end");
+  double total[SITE_COUNT] = {0};
+  long launches[SITE_COUNT] = {0};
+  for (size_t i = 0; i + 1 < st->ev_used; i += 2) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, st->ev_pool[i], st->ev_pool[i + 1]) != hipSuccess) continue;
+    total[st->ev_site[i / 2]] += ms;
+    launches[st->ev_site[i / 2]]++;
+  }
+  st->ev_used = 0;
+  // algorithmic work per launch: 2*M*N*K flops for the GEMMs, causal-half flops for attention
+  // (forward 4*d*S*(S+1)/2 per head, backward 2.5x that as executed by the recompute-in-tile scheme
+  // counts as 2x model flops), bytes moved once for the bandwidth-bound kernels.
+  const double T = st->T, h = st->h, hl = st->hl, F = st->F, Fu = st->llama ? 2.0 * st->F : st->F;
+  const double S = st->cfg.seq_len, B = st->cfg.microbatch_size;
+  const double attn = 4.0 * st->d * (S * (S + 1) / 2) * st->nh * B;
+  double flops[SITE_COUNT] = {0}, bytes[SITE_COUNT] = {0};
+  flops[SITE_QKV_FWD] = flops[SITE_QKV_WGRAD] = flops[SITE_QKV_DGRAD] = 2 * T * h * 3 * hl;
+  flops[SITE_WO_FWD] = flops[SITE_WO_WGRAD] = flops[SITE_WO_DGRAD] = 2 * T * hl * h;
+  flops[SITE_FC1_FWD] = flops[SITE_FC1_WGRAD] = flops[SITE_FC1_DGRAD] = 2 * T * h * Fu;
+  flops[SITE_FC2_FWD] = flops[SITE_FC2_WGRAD] = flops[SITE_FC2_DGRAD] = 2 * T * F * h;
+  flops[SITE_ATTN_FWD] = attn;
+  flops[SITE_ATTN_BWD] = 2 * attn;
+  bytes[SITE_NORM_FWD] = 4 * T * h + 8 * T;
+  bytes[SITE_NORM_BWD] = 8 * T * h + 8 * T;
+  bytes[SITE_ROPE] = 2 * (2 * T * 2 * hl);
+  bytes[SITE_SWIGLU_FWD] = 2 * T * 3 * F;
+  bytes[SITE_SWIGLU_BWD] = 2 * T * 5 * F;
+  int n = 0;
+  for (int sidx = 0; sidx < SITE_COUNT && n < capacity; sidx++) {
+    if (!launches[sidx]) continue;
+    ah_trace_entry_t& o = out[n++];
+    snprintf(o.name, sizeof o.name, "%s", kSiteNames[sidx]);
+    o.launches = launches[sidx];
+    o.total_ms = total[sidx];
+    o.flops_per_launch = flops[sidx];
+    o.bytes_per_launch = bytes[sidx];
+  }
+  *n_out = n;
   return AH_OK;
 }
 

@@ -1,0 +1,105 @@
+"""CPU-side checks of the boundary: the library loads, exports every declared
+symbol, validates configurations, and its byte accounting obeys the memory
+model's identities (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2512_20953_amd as P
+from paper_2512_20953_amd.binding import query_sizes
+from synth import stage_inputs as SI
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "ah_stage.h")).read()
+    names = set(re.findall(r"^(?:int|const char\*)\s+(ah_[a-z_0-9]+)\s*\(", hdr, flags=re.M))
+    assert len(names) >= 16
+    assert {"ah_stage_create", "ah_stage_forward", "ah_stage_backward", "ah_stage_grads", "ah_stage_profile"} <= names
+    lib = ctypes.CDLL(P.library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def _cfg(name, **kw):
+    w = dict(SI.WORKLOADS[name], **kw)
+    return P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
+                              head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
+                              max_in_flight=w.get("max_in_flight", 1), recompute=w["recompute"])
+
+
+@pytest.mark.parametrize("name", list(SI.WORKLOADS))
+def test_all_workloads_are_supported_and_sized(name):
+    w = SI.WORKLOADS[name]
+    s = query_sizes(_cfg(name))
+    nh, hl, F = SI.local_dims(w)
+    h = w["hidden"]
+    if w["arch"] == "gpt":
+        per_layer = 6 * h + h * 3 * hl + 3 * hl + hl * h + h * F + F + F * h
+    else:
+        per_layer = 2 * h + h * 3 * hl + hl * h + 3 * h * F
+    assert s["param_elems"] == per_layer * w["n_layers"]
+    assert s["param_bytes"] == 2 * s["param_elems"] and s["grad_bytes"] == 4 * s["param_elems"]
+    # memory is additive in the layer count (Section III-D, memory profiling)
+    assert s["activation_bytes_per_slot"] == w["n_layers"] * s["activation_bytes_per_layer_per_slot"]
+    s1 = query_sizes(_cfg(name, n_layers=1))
+    assert s1["activation_bytes_per_layer_per_slot"] == s["activation_bytes_per_layer_per_slot"]
+    assert s1["workspace_bytes"] == s["workspace_bytes"]
+    T = w["mb"] * w["seq"]
+    if w["recompute"]:
+        assert s["activation_bytes_per_layer_per_slot"] == 2 * T * h
+    else:
+        saved = 2 * T * (4 * h + 4 * hl + 2 * F) + 4 * T * nh + 16 * T   # bf16 tensors + lse + two (mean, rstd) pairs
+        assert s["activation_bytes_per_layer_per_slot"] == saved
+
+
+def test_known_sizes_of_the_benchmark_workload():
+    s = query_sizes(_cfg("gpt7b_tp2"))
+    assert s["param_elems"] == 4 * 100_702_208
+    assert 1.33e9 < s["activation_bytes_per_slot"] < 1.36e9
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(head_dim=32), 5), (dict(hidden=200), 5), (dict(seq=100), 5), (dict(ffn=1000), 5),
+    (dict(tp=3), 1), (dict(n_layers=0), 1), (dict(mb=0), 1), (dict(max_in_flight=0), 1), (dict(recompute=2), 1),
+])
+def test_bad_configurations_are_refused(kw, status):
+    with pytest.raises(P.AhError) as e:
+        query_sizes(_cfg("tiny", **kw))
+    assert e.value.status == status
+    assert len(str(e.value)) > 10
+
+
+def test_struct_size_is_checked():
+    c = _cfg("tiny")
+    c.struct_size = 8
+    with pytest.raises(P.AhError) as e:
+        query_sizes(c)
+    assert e.value.status == 1
+
+
+def test_create_refuses_missing_or_misaligned_buffers():
+    from paper_2512_20953_amd.binding import _Buffers, lib
+    c = _cfg("tiny")
+    h = ctypes.c_void_p()
+    assert lib.ah_stage_create(ctypes.byref(c), ctypes.byref(_Buffers(0, 0, 0, 0)), ctypes.byref(h)) == 1
+    assert lib.ah_stage_create(ctypes.byref(c), ctypes.byref(_Buffers(256, 512, 768, 1000)), ctypes.byref(h)) == 1
+    assert b"aligned" in lib.ah_last_error()
+    # well-formed pointers: the handle is host metadata only, no device access
+    assert lib.ah_stage_create(ctypes.byref(c), ctypes.byref(_Buffers(256, 512, 768, 1024)), ctypes.byref(h)) == 0
+    off, r, cc = ctypes.c_uint64(), ctypes.c_int32(), ctypes.c_int32()
+    assert lib.ah_stage_param_layout(h, 1, P.PARAM_INDEX["w2"], ctypes.byref(off), ctypes.byref(r), ctypes.byref(cc)) == 0
+    assert (r.value, cc.value) == (1024, 256)
+    assert lib.ah_stage_param_layout(h, 2, 0, ctypes.byref(off), ctypes.byref(r), ctypes.byref(cc)) == 1
+    assert lib.ah_stage_destroy(h) == 0
+
+
+def test_gemm_entry_points_refuse_bad_shapes_without_touching_the_device():
+    from paper_2512_20953_amd.binding import lib
+    assert lib.ah_gemm_nn(1, 1, None, 1, 100, 128, 128, None) == 5
+    assert lib.ah_gemm_nt(None, 1, 1, 128, 128, 128, None) == 1
+    assert lib.ah_gemm_tn(1, 1, 1, 128, 128, 128, 2, None) == 1
+    assert lib.ah_attention_fwd(1, 1, 1, 1, 100, 1, 128, None) == 5
