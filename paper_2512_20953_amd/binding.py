@@ -67,6 +67,10 @@ def _load():
     if not os.path.exists(path):
         raise ImportError("libahstage.so is not built: run `python -m paper_2512_20953_amd.build` "
                           "(or __graft_entry__.build()); there is no fallback implementation")
+    # PyTorch ships its own copy of the HIP runtime and must be loaded first: the dynamic linker
+    # then resolves this library's runtime dependency to that same copy.  Loaded the other way
+    # round the process ends up with two runtimes, and the second one finds no device.
+    import torch  # noqa: F401
     L = C.CDLL(path)
     L.ah_last_error.restype = C.c_char_p
     vp, i = C.c_void_p, C.c_int

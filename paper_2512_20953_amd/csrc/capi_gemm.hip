@@ -8,6 +8,7 @@ using namespace ah;
 static const char* kShapeMsg = "M, N, K must be positive multiples of 128";
 
 extern "C" int ah_gemm_nn(const void* A, const void* B, const void* bias, void* C, int M, int N, int K, void* stream) {
+  discard_stale_hip_error();
   if (!A || !B || !C) return set_error(AH_EINVAL, "ah_gemm_nn: NULL pointer");
   if (!gemm_shape_ok(M, N, K)) return set_error(AH_EUNSUPPORTED, "ah_gemm_nn: %s", kShapeMsg);
   GemmArgs g = {};
@@ -17,6 +18,7 @@ extern "C" int ah_gemm_nn(const void* A, const void* B, const void* bias, void* 
 }
 
 extern "C" int ah_gemm_nt(const void* A, const void* B, void* C, int M, int N, int K, void* stream) {
+  discard_stale_hip_error();
   if (!A || !B || !C) return set_error(AH_EINVAL, "ah_gemm_nt: NULL pointer");
   if (!gemm_shape_ok(M, N, K)) return set_error(AH_EUNSUPPORTED, "ah_gemm_nt: %s", kShapeMsg);
   GemmArgs g = {};
@@ -26,6 +28,7 @@ extern "C" int ah_gemm_nt(const void* A, const void* B, void* C, int M, int N, i
 }
 
 extern "C" int ah_gemm_tn(const void* A, const void* B, float* C, int M, int N, int K, int beta, void* stream) {
+  discard_stale_hip_error();
   if (!A || !B || !C) return set_error(AH_EINVAL, "ah_gemm_tn: NULL pointer");
   if (beta != 0 && beta != 1) return set_error(AH_EINVAL, "ah_gemm_tn: beta must be 0 or 1");
   if (!gemm_shape_ok(M, N, K)) return set_error(AH_EUNSUPPORTED, "ah_gemm_tn: %s", kShapeMsg);

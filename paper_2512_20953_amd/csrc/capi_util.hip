@@ -5,6 +5,7 @@
 
 namespace ah {
 static thread_local char g_err[512] = "";
+thread_local const char* g_where = "";
 
 int set_error(int status, const char* fmt, ...) {
   va_list ap;
@@ -16,7 +17,7 @@ int set_error(int status, const char* fmt, ...) {
 
 int hip_status(hipError_t e, const char* what) {
   if (e == hipSuccess) return AH_OK;
-  return set_error(AH_EDEVICE, "%s: %s", what, hipGetErrorString(e));
+  return set_error(AH_EDEVICE, "%s: %s (hipError %d) in %.200s", what, hipGetErrorString(e), (int)e, g_where);
 }
 }  // namespace ah
 

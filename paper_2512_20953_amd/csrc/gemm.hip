@@ -19,46 +19,48 @@
 
 namespace ah {
 
-constexpr int BK = 64;  // k-extent of one LDS stage (128 bytes of bf16)
+constexpr int BK = 32;  // k-extent of one LDS stage (64 bytes of bf16)
+constexpr int NS = 4;   // stages in the LDS ring: loads run 3 stages ahead of the MFMAs
 
 // ---------------------------------------------------------------------------
 // LDS layouts (all permutations are of 16-byte pieces, the unit of the loader)
-//  k-contiguous tile: [rows][64 k]; row = 128 B = 8 pieces; piece p of row r is
-//    stored at piece p ^ ((r >> 1) & 7): 16 consecutive rows hit 16 distinct
-//    bank groups for the 16-byte fragment reads.
-//  k-strided tile: [64 k][W cols]; row = 2W bytes; the 64-byte granule g of row
+//  k-contiguous tile: [rows][32 k]; row = 64 B = 4 pieces; piece p of row r is
+//    stored at piece p ^ ((r >> 2) & 3): 16 consecutive rows hit 16 distinct
+//    16-byte bank groups for the fragment reads.
+//  k-strided tile: [32 k][W cols]; row = 2W bytes; the 64-byte granule g of row
 //    k is stored at granule g ^ (k & 3): the 4 rows x 64 B that half a wave
 //    fetches in one transposing read cover all banks once.
 // ---------------------------------------------------------------------------
 template <int W, bool KS>
-__device__ __forceinline__ uint32_t loader_src_offset(int chunk, int lane, int ld) {
+__device__ __forceinline__ uint32_t loader_src_offset(int chunk, int lane, int ld) {  // in bytes
   const int pos = chunk * 1024 + lane * 16;
   if (!KS) {
-    const int r = pos >> 7, q = (pos >> 4) & 7;
-    const int p = q ^ ((r >> 1) & 7);
-    return (uint32_t)(r * ld + p * 8);
+    const int r = pos >> 6, q = (pos >> 4) & 3;
+    const int p = q ^ ((r >> 2) & 3);
+    return (uint32_t)(r * ld + p * 8) * 2u;
   } else {
     constexpr int RB = W * 2;
     const int k = pos / RB, q = (pos % RB) >> 4;
     const int p = q ^ ((k & 3) << 2);
-    return (uint32_t)(k * ld + p * 8);
+    return (uint32_t)(k * ld + p * 8) * 2u;
   }
 }
 
-template <int W, bool KS, int NW>
-__device__ __forceinline__ void issue_tile_loads(const bf16* __restrict__ g, const uint32_t* off, char* __restrict__ lds, int wave) {
+// a W x 32 (or 32 x W) tile is W/16 chunks of 1 KB; wave w moves chunks w, w + NW, ...
+template <int W, int NW>
+__device__ __forceinline__ void issue_tile_loads(const char* __restrict__ g, const uint32_t* off, char* __restrict__ lds, int wave) {
 #pragma unroll
-  for (int i = 0; i < W / 8 / NW; i++) load16_to_lds(g + off[i], lds + (wave + NW * i) * 1024);
+  for (int i = 0; i < W / 16 / NW; i++) load16_to_lds(g + off[i], lds + (wave + NW * i) * 1024);
 }
 
-// fragment (8 k-values for row/col = lane % 32 of a 32-wide block) for k-step ks
+// fragment (8 k-values for row/col = lane % 32 of a 32-wide block) for k-step ks (0 or 1)
 template <int W, bool KS>
 __device__ __forceinline__ bf16x8 read_frag(const char* __restrict__ lds, int base, int blk, int ks, int lane) {
   if (!KS) {
     const int r = base + blk * 32 + (lane & 31);
     const int p = ks * 2 + (lane >> 5);
-    const int q = p ^ ((r >> 1) & 7);
-    return *(const bf16x8*)(lds + r * 128 + q * 16);
+    const int q = p ^ ((r >> 2) & 3);
+    return *(const bf16x8*)(lds + r * 64 + q * 16);
   } else {
     constexpr int RB = W * 2;
     const int k = ks * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
@@ -83,22 +85,20 @@ struct Frags {
   }
 };
 
-// Scheduling hint: spread the NR LDS reads issued for the next k-step between the
-// NM MFMAs of the current one (masks: 0x100 = LDS read, 0x008 = MFMA).
-template <int NR, int NM>
-__device__ __forceinline__ void interleave_reads_with_mfma() {
-  if constexpr (NR >= NM) {
-#pragma unroll
-    for (int i = 0; i < NM; i++) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NR / NM, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < NR; i++) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, NM / NR, 0);
-    }
+// Scheduling hint for one k-step: between consecutive MFMAs (NM of them) place
+// the NV global->LDS loads and the NR LDS reads issued for later steps, the LDS
+// reads within the first three quarters so their latency is covered by the rest.
+// Masks: 0x020 = vector memory read, 0x100 = LDS read, 0x008 = MFMA.
+template <int I, int NM, int NR, int NV>
+__device__ __forceinline__ void interleave() {
+  if constexpr (I < NM) {
+    constexpr int SPAN = NM * 3 / 4 > 0 ? NM * 3 / 4 : 1;
+    constexpr int v = (I + 1) * NV / NM - I * NV / NM;
+    constexpr int r = I < SPAN ? (I + 1) * NR / SPAN - I * NR / SPAN : 0;
+    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
+    if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    interleave<I + 1, NM, NR, NV>();
   }
 }
 
@@ -112,50 +112,53 @@ __device__ __forceinline__ void mma_step(const Frags<BM, BN, WGM, WGN, AKS, BKS>
       acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[tn], f.a[tm], acc[tm][tn], 0, 0, 0);
 }
 
-// One k-tile of the pipeline.  On entry f0 holds the fragments of k-step 0 of
-// (cA, cB).  Starts the loads of the next k-tile into (nA, nB), multiplies the
-// current one while the fragments of each following k-step are fetched, and
-// before the last k-step waits for the next tile (its own loads, then the
-// block barrier) so that f0 can be refilled from (nA, nB) under the last MFMAs.
-// The restrict qualifiers tell the compiler that LDS reads of (cA, cB) never
-// touch the buffers being filled.
+// s_waitcnt immediate: vmcnt = n (6 bits, split), lgkmcnt = 0, expcnt untouched
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
+
+// One stage (32 of k) of the pipeline.  On entry f0 holds the fragments of
+// k-step 0 of the current stage (cA, cB).  Starts the loads of the stage three
+// ahead into the ring slot that the previous stage just vacated (fA, fB),
+// multiplies k-step 0 while fetching k-step 1, then waits until the next stage
+// (nA, nB) has landed for the whole block (own loads by count: two later
+// stages may stay in flight; then the barrier) and refills f0 from it under the
+// MFMAs of k-step 1.  The restrict qualifiers tell the compiler that the three
+// slots are distinct, so LDS reads never wait for the loads in flight.
 template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
-__device__ __forceinline__ void pipe_step(bool prefetch, int dbg, const bf16* gA, const bf16* gB, const uint32_t* offA, const uint32_t* offB,
-                                          char* __restrict__ nA, char* __restrict__ nB, const char* __restrict__ cA,
-                                          const char* __restrict__ cB, Frags<BM, BN, WGM, WGN, AKS, BKS>& f0,
-                                          Frags<BM, BN, WGM, WGN, AKS, BKS>& f1, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32],
-                                          int wave, int wm, int wn, int lane) {
-  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+__device__ __forceinline__ void ring_step(const char* gA, const char* gB, const uint32_t* offA, const uint32_t* offB,
+                                          char* __restrict__ fA, char* __restrict__ fB, const char* __restrict__ cA,
+                                          const char* __restrict__ cB, const char* __restrict__ nA, const char* __restrict__ nB,
+                                          Frags<BM, BN, WGM, WGN, AKS, BKS>& f0, Frags<BM, BN, WGM, WGN, AKS, BKS>& f1,
+                                          f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], int wave, int wm, int wn, int lane) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
   constexpr int NR = TM * (AKS ? 2 : 1) + TN * (BKS ? 2 : 1), NM = TM * TN;
-  if (prefetch) {
-    issue_tile_loads<BM, AKS, WGM * WGN>(gA, offA, nA, wave);
-    issue_tile_loads<BN, BKS, WGM * WGN>(gB, offB, nB, wave);
-  }
-  if (dbg < 3) f1.load(cA, cB, 1, wm, wn, lane);
+  constexpr int LPS = (BM + BN) / 16 / NW;  // loads per stage per wave
+  issue_tile_loads<BM, NW>(gA, offA, fA, wave);
+  issue_tile_loads<BN, NW>(gB, offB, fB, wave);
+  f1.load(cA, cB, 1, wm, wn, lane);
   mma_step<BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
-  interleave_reads_with_mfma<NR, NM>();
-  if (dbg < 3) f0.load(cA, cB, 2, wm, wn, lane);
+  interleave<0, NM, NR, LPS>();
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+  __builtin_amdgcn_s_barrier();
+  f0.load(nA, nB, 0, wm, wn, lane);
   mma_step<BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
-  interleave_reads_with_mfma<NR, NM>();
-  if (dbg < 3) f1.load(cA, cB, 3, wm, wn, lane);
-  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
-  interleave_reads_with_mfma<NR, NM>();
-  if (dbg < 2) {
-    __builtin_amdgcn_s_waitcnt(0);  // own loads of the next tile have landed, own reads of this one are done
-    __syncthreads();
-  }
-  if (dbg < 3) f0.load(nA, nB, 0, wm, wn, lane);
-  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
-  interleave_reads_with_mfma<NR, NM>();
+  interleave<0, NM, NR, 0>();
 }
 
 template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
-  __shared__ __attribute__((aligned(1024))) char sA0[BM * 128];
-  __shared__ __attribute__((aligned(1024))) char sA1[BM * 128];
-  __shared__ __attribute__((aligned(1024))) char sB0[BN * 128];
-  __shared__ __attribute__((aligned(1024))) char sB1[BN * 128];
+  constexpr int LPS = (BM + BN) / 16 / NW;
+  // ring slot t: A tile at t * SLOT, B tile behind it; the epilogue reuses the ring as staging space
+  constexpr int SLOT = (BM + BN) * 64;
+  __shared__ __attribute__((aligned(1024))) char ring[NS * SLOT];
+  char* const sA0 = ring;
+  char* const sB0 = ring + BM * 64;
+  char* const sA1 = ring + SLOT;
+  char* const sB1 = ring + SLOT + BM * 64;
+  char* const sA2 = ring + 2 * SLOT;
+  char* const sB2 = ring + 2 * SLOT + BM * 64;
+  char* const sA3 = ring + 3 * SLOT;
+  char* const sB3 = ring + 3 * SLOT + BM * 64;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in scalar registers
@@ -176,16 +179,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   const int m0 = (first_m + in_group % gsize) * BM;
   const int n0 = (in_group / gsize) * BN;
 
-  const bf16* gA = (const bf16*)g.A + (AKS ? (size_t)m0 : (size_t)m0 * g.lda);
-  const bf16* gB = (const bf16*)g.B + (BKS ? (size_t)n0 : (size_t)n0 * g.ldb);
-  const size_t stepA = AKS ? (size_t)BK * g.lda : (size_t)BK;
-  const size_t stepB = BKS ? (size_t)BK * g.ldb : (size_t)BK;
+  const char* gA = (const char*)((const bf16*)g.A + (AKS ? (size_t)m0 : (size_t)m0 * g.lda));
+  const char* gB = (const char*)((const bf16*)g.B + (BKS ? (size_t)n0 : (size_t)n0 * g.ldb));
+  const size_t stepA = (AKS ? (size_t)BK * g.lda : (size_t)BK) * 2;  // bytes per stage
+  const size_t stepB = (BKS ? (size_t)BK * g.ldb : (size_t)BK) * 2;
 
-  uint32_t offA[BM / 8 / NW], offB[BN / 8 / NW];
+  uint32_t offA[BM / 16 / NW], offB[BN / 16 / NW];
 #pragma unroll
-  for (int i = 0; i < BM / 8 / NW; i++) offA[i] = loader_src_offset<BM, AKS>(wave + NW * i, lane, g.lda);
+  for (int i = 0; i < BM / 16 / NW; i++) offA[i] = loader_src_offset<BM, AKS>(wave + NW * i, lane, g.lda);
 #pragma unroll
-  for (int i = 0; i < BN / 8 / NW; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
+  for (int i = 0; i < BN / 16 / NW; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -195,80 +198,127 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  const int nk = g.K / BK;
-  issue_tile_loads<BM, AKS, NW>(gA, offA, sA0, wave);
-  issue_tile_loads<BN, BKS, NW>(gB, offB, sB0, wave);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
+  // nk is a multiple of 4 (K is a multiple of 128).  Stage t lives in ring slot t % 4.
+  const int nk = g.K / BK, last = nk - 1;
+  issue_tile_loads<BM, NW>(gA, offA, sA0, wave);
+  issue_tile_loads<BN, NW>(gB, offB, sB0, wave);
+  issue_tile_loads<BM, NW>(gA + stepA, offA, sA1, wave);
+  issue_tile_loads<BN, NW>(gB + stepB, offB, sB1, wave);
+  issue_tile_loads<BM, NW>(gA + 2 * stepA, offA, sA2, wave);
+  issue_tile_loads<BN, NW>(gB + 2 * stepB, offB, sB2, wave);
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+  __builtin_amdgcn_s_barrier();
 
   Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
   f0.load(sA0, sB0, 0, wm, wn, lane);
-  // nk is even (K is a multiple of 128): two k-tiles per trip, buffers alternate
-  for (int kt = 0; kt < nk; kt += 2) {
-    gA += stepA;
-    gB += stepB;
-    pipe_step<BM, BN, WGM, WGN, AKS, BKS>(!g.debug_noload, g.debug_noload, gA, gB, offA, offB, sA1, sB1, sA0, sB0, f0, f1, acc, wave, wm, wn, lane);
-    gA += stepA;
-    gB += stepB;
-    pipe_step<BM, BN, WGM, WGN, AKS, BKS>(!g.debug_noload && kt + 2 < nk, g.debug_noload, gA, gB, offA, offB, sA0, sB0, sA1, sB1, f0, f1, acc, wave,
-                                          wm, wn, lane);
+  // The stage loaded during step t is min(t + 3, last): past the end the last stage is
+  // fetched again into a dead slot, which keeps the in-flight load count uniform.
+#define AH_STAGE_PTRS(t) gA + (size_t)min((t) + 3, last) * stepA, gB + (size_t)min((t) + 3, last) * stepB
+  for (int t = 0; t < nk; t += 4) {
+    ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t), offA, offB, sA3, sB3, sA0, sB0, sA1, sB1, f0, f1, acc, wave, wm, wn, lane);
+    ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 1), offA, offB, sA0, sB0, sA1, sB1, sA2, sB2, f0, f1, acc, wave, wm, wn, lane);
+    ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 2), offA, offB, sA1, sB1, sA2, sB2, sA3, sB3, f0, f1, acc, wave, wm, wn, lane);
+    ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 3), offA, offB, sA2, sB2, sA3, sB3, sA0, sB0, f0, f1, acc, wave, wm, wn, lane);
   }
+#undef AH_STAGE_PTRS
+  __builtin_amdgcn_s_waitcnt(0);  // drain the redundant tail loads before the block's LDS is released
 
-  // ---- epilogue: lane holds C[m][n .. n+3] for 4 column groups of each 32x32 block
+  // ---- epilogue.  A lane holds C[m][n .. n+3] for 4 column groups of each 32x32 block: stores
+  // straight from that layout would touch 32 rows per instruction, 16 bytes each.  Instead each
+  // wave passes its sub-tile through a private LDS strip, 32 rows at a time in fp32, and reads it
+  // back row-major, so that every global access is 16 bytes per lane and whole rows per 16 lanes.
+  constexpr int WN = BN / WGN, WM = BM / WGM;
+  constexpr int ROWB = WN * 4 + 16;                // padded strip row
+  static_assert(NW * 32 * ROWB <= NS * SLOT, "staging strips must fit in the ring");
+  __syncthreads();                                  // every wave is done with the ring
+  char* strip = ring + wave * (32 * ROWB);
   const bf16* bias = (const bf16*)g.bias;
   const bf16* aux = (const bf16*)g.aux;
-  const bool has_bias = (EPI != EPI_GELU_BWD && EPI != EPI_F32_ACC) && bias != nullptr;
+  const bool has_bias = (EPI == EPI_BF16 || EPI == EPI_GELU || EPI == EPI_RESID) && bias != nullptr;
+  constexpr int PPR = WN / 8;                       // 8-column pieces per strip row
+  constexpr int NIT = 32 * PPR / 64;                // pieces per lane per strip
+  static_assert(64 % PPR == 0, "a lane keeps its column piece across iterations");
+  const int cp = lane % PPR, row0 = lane / PPR;     // piece it*64 + lane -> row row0 + it * (64 / PPR)
+  const int n = n0 + wn * WN + cp * 8;
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (has_bias) {
+    const bf16x8 b = *(const bf16x8*)(bias + n);
 #pragma unroll
-  for (int tn = 0; tn < TN; tn++) {
+    for (int i = 0; i < 8; i++) bv[i] = bf2f(b[i]);
+  }
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const int n = n0 + wn * (BN / WGN) + tn * 32 + 8 * q + 4 * (lane >> 5);
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (has_bias) {
-        bf16x4 b = *(const bf16x4*)(bias + n);
+  for (int tm = 0; tm < TM; tm++) {
+    const int mbase = m0 + wm * WM + tm * 32 + row0;
+    // operands of the epilogue that come from memory: issue their loads before the strip round trip
+    bf16x8 ax[NIT];
+    f32x4 old0[NIT], old1[NIT];
+    if (EPI == EPI_RESID || EPI == EPI_GELU_BWD) {
 #pragma unroll
-        for (int i = 0; i < 4; i++) bv[i] = bf2f(b[i]);
+      for (int it = 0; it < NIT; it++) ax[it] = *(const bf16x8*)(aux + (size_t)(mbase + it * (64 / PPR)) * g.ld_aux + n);
+    }
+    if (EPI == EPI_F32_ACC) {
+#pragma unroll
+      for (int it = 0; it < NIT; it++) {
+        const float* cptr = (const float*)g.C + (size_t)(mbase + it * (64 / PPR)) * g.ldc + n;
+        old0[it] = *(const f32x4*)cptr;
+        old1[it] = *(const f32x4*)(cptr + 4);
       }
+    }
 #pragma unroll
-      for (int tm = 0; tm < TM; tm++) {
-        const int m = m0 + wm * (BM / WGM) + tm * 32 + (lane & 31);
-        float v[4];
+    for (int tn = 0; tn < TN; tn++)
 #pragma unroll
-        for (int i = 0; i < 4; i++) v[i] = acc[tm][tn][4 * q + i] + bv[i];
+      for (int q = 0; q < 4; q++) {
+        const int col = tn * 32 + 8 * q + 4 * (lane >> 5);
+        f32x4 v = {acc[tm][tn][4 * q], acc[tm][tn][4 * q + 1], acc[tm][tn][4 * q + 2], acc[tm][tn][4 * q + 3]};
+        *(f32x4*)(strip + (lane & 31) * ROWB + col * 4) = v;
+      }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < NIT; it++) {
+      const int row = row0 + it * (64 / PPR);
+      const f32x4 lo = *(const f32x4*)(strip + row * ROWB + cp * 32);
+      const f32x4 hi = *(const f32x4*)(strip + row * ROWB + cp * 32 + 16);
+      float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      const size_t m = (size_t)(mbase + it * (64 / PPR));
+      if (EPI == EPI_F32_ACC || EPI == EPI_F32_SET) {
+        float* cptr = (float*)g.C + m * g.ldc + n;
         if (EPI == EPI_F32_ACC) {
-          float* cp = (float*)g.C + (size_t)m * g.ldc + n;
-          if (g.beta) {
-            f32x4 old = *(const f32x4*)cp;
 #pragma unroll
-            for (int i = 0; i < 4; i++) v[i] += old[i];
-          }
-          f32x4 o = {v[0], v[1], v[2], v[3]};
-          *(f32x4*)cp = o;
-        } else {
-          if (EPI == EPI_RESID) {
-            bf16x4 r = *(const bf16x4*)(aux + (size_t)m * g.ld_aux + n);
+          for (int i = 0; i < 4; i++) { v[i] += old0[it][i]; v[4 + i] += old1[it][i]; }
+        }
+        *(f32x4*)cptr = f32x4{v[0], v[1], v[2], v[3]};
+        *(f32x4*)(cptr + 4) = f32x4{v[4], v[5], v[6], v[7]};
+      } else {
 #pragma unroll
-            for (int i = 0; i < 4; i++) v[i] += bf2f(r[i]);
-          }
-          if (EPI == EPI_GELU_BWD) {
-            bf16x4 u = *(const bf16x4*)(aux + (size_t)m * g.ld_aux + n);
+        for (int i = 0; i < 8; i++) v[i] += bv[i];
+        if (EPI == EPI_RESID) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) v[i] *= gelu_grad_f(bf2f(u[i]));
-          }
-          bf16x4 o = {f2bf(v[0]), f2bf(v[1]), f2bf(v[2]), f2bf(v[3])};
-          *(bf16x4*)((bf16*)g.C + (size_t)m * g.ldc + n) = o;
-          if (EPI == EPI_GELU) {
-            bf16x4 o2 = {f2bf(gelu_f(v[0])), f2bf(gelu_f(v[1])), f2bf(gelu_f(v[2])), f2bf(gelu_f(v[3]))};
-            *(bf16x4*)((bf16*)g.C2 + (size_t)m * g.ldc + n) = o2;
-          }
+          for (int i = 0; i < 8; i++) v[i] += bf2f(ax[it][i]);
+        }
+        if (EPI == EPI_GELU_BWD) {
+#pragma unroll
+          for (int i = 0; i < 8; i++) v[i] *= gelu_grad_f(bf2f(ax[it][i]));
+        }
+        bf16x8 o;
+#pragma unroll
+        for (int i = 0; i < 8; i++) o[i] = f2bf(v[i]);
+        *(bf16x8*)((bf16*)g.C + m * g.ldc + n) = o;
+        if (EPI == EPI_GELU) {
+          bf16x8 o2;
+#pragma unroll
+          for (int i = 0; i < 8; i++) o2[i] = f2bf(gelu_f(v[i]));
+          *(bf16x8*)((bf16*)g.C2 + m * g.ldc + n) = o2;
         }
       }
     }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));  // strip reads are in registers before the next 32 rows overwrite it
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
 bool gemm_shape_ok(int M, int N, int K) {
-  return M > 0 && N > 0 && K > 0 && (M % 128) == 0 && (N % 128) == 0 && (K % (2 * BK)) == 0;
+  return M > 0 && N > 0 && K > 0 && (M % 128) == 0 && (N % 128) == 0 && (K % (NS * BK)) == 0;
 }
 
 namespace {
@@ -277,8 +327,7 @@ namespace {
 // ceil(tiles / 256) rounds of one tile's time.  Relative tile costs (per output
 // element) are measured constants: smaller tiles re-read more from LDS and L2.
 struct TileCfg { int bm, bn, wgm, wgn; float cost; };
-const TileCfg kTiles[] = {{256, 256, 2, 2, 1.00f}, {256, 128, 2, 2, 1.12f}, {128, 256, 2, 2, 1.12f}, {128, 128, 2, 2, 1.35f},
-                          {256, 256, 2, 4, 1.00f}, {256, 256, 4, 2, 1.00f}, {256, 128, 4, 2, 1.12f}, {128, 256, 2, 4, 1.12f}};
+const TileCfg kTiles[] = {{256, 256, 2, 2, 1.00f}, {256, 128, 2, 2, 1.12f}, {128, 256, 2, 2, 1.12f}, {128, 128, 2, 2, 1.35f}};
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int kAutoTiles = 4;  // the automatic choice looks at the first kAutoTiles entries
 
@@ -314,21 +363,13 @@ hipError_t run_tile(int t, const GemmArgs& a, hipStream_t s) {
     case 0: return run<256, 256, 2, 2, AKS, BKS, EPI>(a, s);
     case 1: return run<256, 128, 2, 2, AKS, BKS, EPI>(a, s);
     case 2: return run<128, 256, 2, 2, AKS, BKS, EPI>(a, s);
-    case 3: return run<128, 128, 2, 2, AKS, BKS, EPI>(a, s);
-    case 4: return run<256, 256, 2, 4, AKS, BKS, EPI>(a, s);
-    case 5: return run<256, 256, 4, 2, AKS, BKS, EPI>(a, s);
-    case 6: return run<256, 128, 4, 2, AKS, BKS, EPI>(a, s);
-    default: return run<128, 256, 2, 4, AKS, BKS, EPI>(a, s);
+    default: return run<128, 128, 2, 2, AKS, BKS, EPI>(a, s);
   }
 }
 
 }  // namespace
 
-hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in, hipStream_t s) {
-  GemmArgs a = a_in;
-  static int dbg = -1;
-  if (dbg < 0) dbg = getenv("AH_GEMM_NOLOAD") ? atoi(getenv("AH_GEMM_NOLOAD")) : 0;
-  a.debug_noload = dbg;
+hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
   if (!gemm_shape_ok(a.M, a.N, a.K)) return hipErrorInvalidValue;
   const int t = pick_tile(a.M, a.N);
   if (t < 0) return hipErrorInvalidValue;
@@ -340,7 +381,7 @@ hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in
     if (epi == EPI_BF16) return run_tile<false, false, EPI_BF16>(t, a, s);
     if (epi == EPI_GELU_BWD) return run_tile<false, false, EPI_GELU_BWD>(t, a, s);
   } else if (layout == GEMM_TN) {
-    if (epi == EPI_F32_ACC) return run_tile<true, true, EPI_F32_ACC>(t, a, s);
+    if (epi == EPI_F32_ACC) return a.beta ? run_tile<true, true, EPI_F32_ACC>(t, a, s) : run_tile<true, true, EPI_F32_SET>(t, a, s);
   }
   return hipErrorInvalidValue;
 }

@@ -11,7 +11,8 @@ enum GemmEpilogue {
   EPI_GELU = 1,      // C = u = acc + bias[n];  C2 = gelu(u)
   EPI_RESID = 2,     // C = acc (+ bias[n]) + aux[m, n]
   EPI_GELU_BWD = 3,  // C = acc * gelu'(aux[m, n])
-  EPI_F32_ACC = 4    // C (fp32) = beta * C + acc
+  EPI_F32_ACC = 4,   // C (fp32) = beta * C + acc  (callers use this one; beta selects the kernel)
+  EPI_F32_SET = 5    // C (fp32) = acc            (internal: EPI_F32_ACC with beta == 0)
 };
 
 struct GemmArgs {
@@ -24,7 +25,6 @@ struct GemmArgs {
   int lda, ldb, ldc, ld_aux;
   int M, N, K;
   int beta;
-  int debug_noload;  // timing experiment only: skip the main-loop loads (results are garbage)
 };
 
 // M, N, K multiples of 128, all leading dimensions multiples of 8.
@@ -51,6 +51,8 @@ hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* par
 int colsum_blocks(int T);
 // rotary embedding in place on the Q and K blocks of qkv[T, 3*nh*d]; sign = +1 forward, -1 backward
 hipError_t launch_rope(void* qkv, const float* cos_sin, int T, int S, int nh, int d, float sign, hipStream_t s);
+// device-to-device copy of a multiple of 16 bytes
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 // m = silu(gu[:, :F]) * gu[:, F:]
 hipError_t launch_swiglu_fwd(const void* gu, void* m, int T, int F, hipStream_t s);
 // dgu from dm and gu

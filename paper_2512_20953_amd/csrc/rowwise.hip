@@ -211,6 +211,12 @@ __global__ __launch_bounds__(NT) void rope_kernel(bf16* __restrict__ qkv, const 
   *(bf16x8*)(p + half) = ob;
 }
 
+// ---------------------------------------------------------------- plain copy, 16 bytes per lane
+__global__ __launch_bounds__(NT) void copy16_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  const size_t i = (size_t)blockIdx.x * NT + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+
 // ---------------------------------------------------------------- SwiGLU
 __global__ __launch_bounds__(NT) void swiglu_fwd_kernel(const bf16* __restrict__ gu, bf16* __restrict__ m, long n8, int F) {
   const long idx = (long)blockIdx.x * NT + threadIdx.x;
@@ -309,6 +315,13 @@ hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* par
 hipError_t launch_rope(void* qkv, const float* cos_sin, int T, int S, int nh, int d, float sign, hipStream_t s) {
   const long total = (long)T * 2 * nh * (d / 16);
   hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((total + NT - 1) / NT)), dim3(NT), 0, s, (bf16*)qkv, cos_sin, T, S, nh, d, sign);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  if (bytes % 16) return hipErrorInvalidValue;
+  const size_t n16 = bytes / 16;
+  hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)((n16 + NT - 1) / NT)), dim3(NT), 0, s, (const uint4*)src, (uint4*)dst, n16);
   return hipGetLastError();
 }
 

@@ -248,12 +248,14 @@ ActPtrs act_ptrs(const ah_stage* s, int slot, int layer) {
 #define TIMED(site, expr)                \
   do {                                   \
     SiteTimer t_(s, site, st);           \
+    g_where = #expr;                     \
     hipError_t e_ = (expr);              \
     if (e_ != hipSuccess) return e_;     \
   } while (0)
 
 #define TRY(expr)                        \
   do {                                   \
+    g_where = #expr;                     \
     hipError_t e_ = (expr);              \
     if (e_ != hipSuccess) return e_;     \
   } while (0)
@@ -353,7 +355,7 @@ hipError_t ensure_rope(ah_stage* s, hipStream_t st) {
 hipError_t stage_forward(ah_stage* s, int slot, const void* x, void* y, hipStream_t st, hipEvent_t* ev) {
   TRY(ensure_rope(s, st));
   const size_t xbytes = (size_t)s->T * s->h * 2;
-  TRY(hipMemcpyAsync(act_ptrs(s, slot, 0).x_in, x, xbytes, hipMemcpyDeviceToDevice, st));
+  TRY(launch_copy(act_ptrs(s, slot, 0).x_in, x, xbytes, st));
   if (ev) TRY(hipEventRecord(ev[0], st));
   for (int l = 0; l < s->L; l++) {
     const ActPtrs a = act_ptrs(s, slot, l);
@@ -443,6 +445,7 @@ extern "C" int ah_stage_param_layout(const ah_stage_t* st, int layer, int which,
 }
 
 extern "C" int ah_stage_forward(ah_stage_t* st, int slot, const void* x, void* y, void* stream) {
+  discard_stale_hip_error();
   if (!st || !x || !y) return set_error(AH_EINVAL, "ah_stage_forward: NULL argument");
   if (slot < 0 || slot >= (int)st->busy.size()) return set_error(AH_EINVAL, "ah_stage_forward: slot %d out of range [0, %zu)", slot, st->busy.size());
   if (st->busy[slot]) return set_error(AH_ESTATE, "ah_stage_forward: slot %d still holds a micro-batch awaiting backward", slot);
@@ -452,6 +455,7 @@ extern "C" int ah_stage_forward(ah_stage_t* st, int slot, const void* x, void* y
 }
 
 extern "C" int ah_stage_backward(ah_stage_t* st, int slot, const void* dy, void* dx, void* stream) {
+  discard_stale_hip_error();
   if (!st || !dy || !dx) return set_error(AH_EINVAL, "ah_stage_backward: NULL argument");
   if (slot < 0 || slot >= (int)st->busy.size()) return set_error(AH_EINVAL, "ah_stage_backward: slot %d out of range [0, %zu)", slot, st->busy.size());
   if (!st->busy[slot]) return set_error(AH_ESTATE, "ah_stage_backward: slot %d holds no forward pass", slot);
@@ -474,6 +478,7 @@ extern "C" int ah_stage_zero_grads(ah_stage_t* st, void* /*stream*/) {
 }
 
 extern "C" int ah_stage_profile(ah_stage_t* st, int warmup, int iters, ah_stage_profile_t* out) {
+  discard_stale_hip_error();
   if (!st || !out) return set_error(AH_EINVAL, "ah_stage_profile: NULL argument");
   if (out->struct_size != sizeof(ah_stage_profile_t)) return set_error(AH_EINVAL, "ah_stage_profile: struct_size mismatch");
   if (out->n_layers < st->L || !out->fwd_ms || !out->bwd_ms) return set_error(AH_EINVAL, "ah_stage_profile: fwd_ms/bwd_ms must hold n_layers entries");
@@ -598,6 +603,7 @@ extern "C" int ah_stage_trace_end(ah_stage_t* st, ah_trace_entry_t* out, int cap
 }
 
 extern "C" int ah_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, void* stream) {
+  discard_stale_hip_error();
   if (!qkv || !o || !lse) return set_error(AH_EINVAL, "ah_attention_fwd: NULL pointer");
   if (B < 1 || nh < 1 || S < 1 || S % 128 || (d != 64 && d != 128)) return set_error(AH_EUNSUPPORTED, "ah_attention_fwd: need S %% 128 == 0 and d in {64, 128}");
   return hip_status(launch_attention_fwd(qkv, o, lse, B, S, nh, d, (hipStream_t)stream), "ah_attention_fwd");
@@ -605,6 +611,7 @@ extern "C" int ah_attention_fwd(const void* qkv, void* o, float* lse, int B, int
 
 extern "C" int ah_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta, int B,
                                 int S, int nh, int d, void* stream) {
+  discard_stale_hip_error();
   if (!qkv || !o || !lse || !d_o || !dqkv || !delta) return set_error(AH_EINVAL, "ah_attention_bwd: NULL pointer");
   if (B < 1 || nh < 1 || S < 1 || S % 128 || (d != 64 && d != 128)) return set_error(AH_EUNSUPPORTED, "ah_attention_bwd: need S %% 128 == 0 and d in {64, 128}");
   return hip_status(launch_attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, (hipStream_t)stream), "ah_attention_bwd");
