@@ -46,6 +46,8 @@ hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float*
 int norm_bwd_blocks(int T);
 // g[c] = beta * g[c] + sum_b part[b][c]
 hipError_t launch_colsum_finish(const float* part, int nblk, int n, float* g, int beta, hipStream_t s);
+// the three partial arrays a norm backward leaves in `part` -> three gradient vectors in one launch
+hipError_t launch_colsum_finish3(const float* part, int nblk, int n, float* g0, float* g1, float* g2, int beta, hipStream_t s);
 // partial column sums of a bf16 matrix [T, n] -> part[nblk][n]
 hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* part, hipStream_t s);
 int colsum_blocks(int T);

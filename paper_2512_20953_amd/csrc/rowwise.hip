@@ -158,30 +158,54 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(const bf16* __restrict__ d
 }
 
 // ---------------------------------------------------------------- column sums
-// grid (ceil(n / 2048), nblk): thread owns 8 columns, block owns a slab of rows
+// Partial sums: grid (ceil(n / 512), nblk).  A wave owns 512 columns (16 bytes per lane, one
+// contiguous kilobyte per row) and every fourth row of the block's slab; the four waves' sums
+// meet in LDS and leave as one row of part[nblk][n].
+constexpr int CS_ROWS = 64;  // rows per block
 __global__ __launch_bounds__(NT) void colsum_partial_kernel(const bf16* __restrict__ m, int T, int n, int ld,
                                                             float* __restrict__ part) {
-  const int col = (blockIdx.x * NT + threadIdx.x) * 8;
-  if (col >= n) return;
-  const int rpb = (T + gridDim.y - 1) / gridDim.y;
-  const int r0 = blockIdx.y * rpb, r1 = min(T, r0 + rpb);
+  __shared__ float red[3][512];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = blockIdx.x * 512 + lane * 8;
+  const int r0 = blockIdx.y * CS_ROWS, r1 = min(T, r0 + CS_ROWS);
   float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int r = r0; r < r1; r++) {
-    bf16x8 t = *(const bf16x8*)(m + (size_t)r * ld + col);
+  if (col < n) {
+#pragma unroll 4
+    for (int r = r0 + wave; r < r1; r += 4) {
+      bf16x8 t = *(const bf16x8*)(m + (size_t)r * ld + col);
 #pragma unroll
-    for (int j = 0; j < 8; j++) s[j] += bf2f(t[j]);
+      for (int j = 0; j < 8; j++) s[j] += bf2f(t[j]);
+    }
   }
-  float* p = part + (size_t)blockIdx.y * n + col;
+  if (wave > 0) {
 #pragma unroll
-  for (int j = 0; j < 8; j++) p[j] = s[j];
+    for (int j = 0; j < 8; j++) red[wave - 1][lane * 8 + j] = s[j];
+  }
+  __syncthreads();
+  if (wave == 0 && col < n) {
+    float* p = part + (size_t)blockIdx.y * n + col;
+#pragma unroll
+    for (int j = 0; j < 8; j++) p[j] = s[j] + red[0][lane * 8 + j] + red[1][lane * 8 + j] + red[2][lane * 8 + j];
+  }
 }
 
-__global__ __launch_bounds__(NT) void colsum_finish_kernel(const float* __restrict__ part, int nblk, int n,
-                                                           float* __restrict__ g, int beta) {
+// g[c] = beta * g[c] + sum_b part[b][c] for up to three (part, g) pairs that share n and nblk
+struct FinishArgs { const float* part[3]; float* g[3]; };
+__global__ __launch_bounds__(NT) void colsum_finish_kernel(FinishArgs a, int nblk, int n, int beta) {
   const int c = blockIdx.x * NT + threadIdx.x;
   if (c >= n) return;
-  float s = 0.f;
-  for (int b = 0; b < nblk; b++) s += part[(size_t)b * n + c];
+  const float* part = a.part[blockIdx.y];
+  float* g = a.g[blockIdx.y];
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int b = 0;
+  for (; b + 4 <= nblk; b += 4) {
+    s0 += part[(size_t)b * n + c];
+    s1 += part[(size_t)(b + 1) * n + c];
+    s2 += part[(size_t)(b + 2) * n + c];
+    s3 += part[(size_t)(b + 3) * n + c];
+  }
+  for (; b < nblk; b++) s0 += part[(size_t)b * n + c];
+  const float s = (s0 + s1) + (s2 + s3);
   g[c] = beta ? g[c] + s : s;
 }
 
@@ -300,15 +324,22 @@ hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float*
 }
 
 hipError_t launch_colsum_finish(const float* part, int nblk, int n, float* g, int beta, hipStream_t s) {
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + NT - 1) / NT), dim3(NT), 0, s, part, nblk, n, g, beta);
+  FinishArgs a = {{part, nullptr, nullptr}, {g, nullptr, nullptr}};
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + NT - 1) / NT, 1), dim3(NT), 0, s, a, nblk, n, beta);
   return hipGetLastError();
 }
 
-int colsum_blocks(int T) { return T / 16 < 64 ? (T / 16 > 0 ? T / 16 : 1) : 64; }
+hipError_t launch_colsum_finish3(const float* part, int nblk, int n, float* g0, float* g1, float* g2, int beta, hipStream_t s) {
+  FinishArgs a = {{part, part + (size_t)nblk * n, part + (size_t)2 * nblk * n}, {g0, g1, g2}};
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + NT - 1) / NT, 3), dim3(NT), 0, s, a, nblk, n, beta);
+  return hipGetLastError();
+}
+
+int colsum_blocks(int T) { return (T + CS_ROWS - 1) / CS_ROWS; }
 
 hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* part, hipStream_t s) {
-  hipLaunchKernelGGL(colsum_partial_kernel, dim3((n + NT * 8 - 1) / (NT * 8), colsum_blocks(T)), dim3(NT), 0, s,
-                     (const bf16*)m, T, n, ld, part);
+  if (n % 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3((n + 511) / 512, colsum_blocks(T)), dim3(NT), 0, s, (const bf16*)m, T, n, ld, part);
   return hipGetLastError();
 }
 

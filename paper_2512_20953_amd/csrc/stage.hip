@@ -316,11 +316,8 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   }
   // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
   TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part, T, h, st));
-  TIMED(SITE_COLSUM, launch_colsum_finish(part, nb, h, p.g_ln2_g, beta, st));
-  if (!rms) {
-    TIMED(SITE_COLSUM, launch_colsum_finish(part + (size_t)nb * h, nb, h, p.g_ln2_b, beta, st));
-    TIMED(SITE_COLSUM, launch_colsum_finish(part + (size_t)2 * nb * h, nb, h, p.g_b2, beta, st));
-  }
+  if (rms) TIMED(SITE_COLSUM, launch_colsum_finish(part, nb, h, p.g_ln2_g, beta, st));
+  else TIMED(SITE_COLSUM, launch_colsum_finish3(part, nb, h, p.g_ln2_g, p.g_ln2_b, p.g_b2, beta, st));
   // output projection
   TRY(gemm(s, SITE_WO_WGRAD, GEMM_TN, EPI_F32_ACC, a.o, hl, dmid, h, p.g_wo, h, hl, h, T, nullptr, nullptr, 0, nullptr, beta, st));
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
@@ -335,11 +332,8 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   TRY(gemm(s, SITE_QKV_DGRAD, GEMM_NT, EPI_BF16, dbig, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
   // first norm backward; dx = dx_mid + norm_bwd(da); column sums give d(gain), d(offset), d(bo)
   TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part, T, h, st));
-  TIMED(SITE_COLSUM, launch_colsum_finish(part, nb, h, p.g_ln1_g, beta, st));
-  if (!rms) {
-    TIMED(SITE_COLSUM, launch_colsum_finish(part + (size_t)nb * h, nb, h, p.g_ln1_b, beta, st));
-    TIMED(SITE_COLSUM, launch_colsum_finish(part + (size_t)2 * nb * h, nb, h, p.g_bo, beta, st));
-  }
+  if (rms) TIMED(SITE_COLSUM, launch_colsum_finish(part, nb, h, p.g_ln1_g, beta, st));
+  else TIMED(SITE_COLSUM, launch_colsum_finish3(part, nb, h, p.g_ln1_g, p.g_ln1_b, p.g_bo, beta, st));
   return hipSuccess;
 }
 
