@@ -1,0 +1,148 @@
+"""Parity at the full sizes of the workload table, in the launch configuration bench.py times.
+
+The CPU oracle cannot run a whole multi-layer, K-micro-batch iteration of the large stages in test
+time, so full size is covered three ways: (1) each MFMA kernel at the benchmark's shapes against
+oracle values computed for sampled outputs (GEMM entries as float64 dot products, attention for
+sampled heads); (2) one full-size layer of every workload, one micro-batch, forward + backward,
+against the float32 oracle; (3) properties of the complete benchmark iteration that hold at any
+size (bit-reproducibility, finiteness, linear accumulation)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2512_20953_amd as P
+from oracle import stage_ref as R
+from synth import stage_inputs as SI
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_normal(rng, shape, std):
+    return SI.round_bf16((rng.standard_normal(shape, dtype=np.float32) * np.float32(std)))
+
+
+@pytest.mark.parametrize("layout,M,N,K", [
+    ("nn", 4096, 8192, 4096),   # first MLP matrix forward
+    ("nn", 4096, 6144, 4096),   # QKV forward (256x128 tiles)
+    ("nt", 4096, 2048, 4096),   # out-projection input gradient (256x128 tiles)
+    ("nt", 4096, 4096, 8192),   # first MLP matrix input gradient
+    ("tn", 8192, 4096, 4096),   # second MLP matrix weight gradient
+    ("tn", 2048, 4096, 4096),   # out-projection weight gradient
+])
+def test_gemm_at_benchmark_shapes_sampled_entries(layout, M, N, K):
+    rng = np.random.default_rng(7)
+    rows = np.sort(rng.choice(M, 48, replace=False))
+    cols = np.sort(rng.choice(N, 48, replace=False))
+    # also the four corners of the output and of an interior tile
+    rows = np.unique(np.concatenate([rows, [0, 255, 256, M - 1]]))
+    cols = np.unique(np.concatenate([cols, [0, 127, 128, N - 1]]))
+    if layout == "nn":
+        A, B = _bf16_normal(rng, (M, K), 1.0), _bf16_normal(rng, (K, N), 0.02)
+        bias = _bf16_normal(rng, (N,), 0.5)
+        C = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+        P.gemm_nn(U.to_dev(A), U.to_dev(B), U.to_dev(bias), C)
+        ref = A[rows].astype(np.float64) @ B[:, cols].astype(np.float64) + bias[cols].astype(np.float64)
+        tol = 2e-2
+    elif layout == "nt":
+        A, B = _bf16_normal(rng, (M, K), 1.0), _bf16_normal(rng, (N, K), 0.02)
+        C = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+        P.gemm_nt(U.to_dev(A), U.to_dev(B), C)
+        ref = A[rows].astype(np.float64) @ B[cols].astype(np.float64).T
+        tol = 2e-2
+    else:
+        A, B = _bf16_normal(rng, (K, M), 1.0), _bf16_normal(rng, (K, N), 1.0)
+        C0 = rng.standard_normal((M, N), dtype=np.float32)
+        C = torch.from_numpy(C0).cuda()
+        P.gemm_tn(U.to_dev(A), U.to_dev(B), C, 1)
+        ref = C0[np.ix_(rows, cols)].astype(np.float64) + A[:, rows].astype(np.float64).T @ B[:, cols].astype(np.float64)
+        tol = 1e-4   # fp32 output: only the accumulation order differs
+    torch.cuda.synchronize()
+    got = U.to_np(C)[np.ix_(rows, cols)]
+    assert U.rel_l2(got, ref) <= tol
+    assert np.abs(got - ref).max() <= tol * 4 * np.abs(ref).max()
+    if layout == "tn":   # beta = 0 overwrites
+        P.gemm_tn(U.to_dev(A), U.to_dev(B), C, 0)
+        torch.cuda.synchronize()
+        ref0 = A[:, rows].astype(np.float64).T @ B[:, cols].astype(np.float64)
+        assert U.rel_l2(U.to_np(C)[np.ix_(rows, cols)], ref0) <= tol
+
+
+@pytest.mark.parametrize("B,S,nh,d", [(2, 2048, 16, 128), (1, 4096, 32, 128)])
+def test_attention_at_benchmark_shapes_sampled_heads(B, S, nh, d):
+    rng = np.random.default_rng(8)
+    T, hl = B * S, nh * d
+    qkv = _bf16_normal(rng, (T, 3 * hl), 1.0)
+    d_o = _bf16_normal(rng, (T, hl), 1.0)
+    qkv_d, do_d = U.to_dev(qkv), U.to_dev(d_o)
+    o = torch.empty(T, hl, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(B * nh * S, dtype=torch.float32, device="cuda")
+    dqkv = torch.empty(T, 3 * hl, dtype=torch.bfloat16, device="cuda")
+    delta = torch.empty(B * nh * S, dtype=torch.float32, device="cuda")
+    P.attention_fwd(qkv_d, o, lse, B, S, nh, d)
+    P.attention_bwd(qkv_d, o, lse, do_d, dqkv, delta, B, S, nh, d)
+    torch.cuda.synchronize()
+    o_np, dqkv_np, lse_np = U.to_np(o), U.to_np(dqkv), lse.cpu().numpy().reshape(B, nh, S)
+    for (b, j) in [(0, 0), (B - 1, nh - 1), (0, nh // 2)]:
+        rows = slice(b * S, (b + 1) * S)
+        q, k, v = (qkv[rows, blk * hl + j * d: blk * hl + (j + 1) * d].astype(np.float64)[None, None] for blk in range(3))
+        do = d_o[rows, j * d:(j + 1) * d].astype(np.float64)[None, None]
+        ro = R.attention_fwd(q, k, v)[0, 0]
+        rdq, rdk, rdv = (t[0, 0] for t in R.attention_bwd(q, k, v, do))
+        assert U.rel_l2(o_np[rows, j * d:(j + 1) * d], ro) <= 2e-2
+        for blk, ref in enumerate((rdq, rdk, rdv)):
+            assert U.rel_l2(dqkv_np[rows, blk * hl + j * d: blk * hl + (j + 1) * d], ref) <= 3e-2, (b, j, blk)
+        # log-sum-exp of the scaled causal scores, from its definition
+        s = (q[0, 0] @ k[0, 0].T) / np.sqrt(d)
+        s[np.triu_indices(S, 1)] = -np.inf
+        m = s.max(-1)
+        ref_lse = m + np.log(np.exp(s - m[:, None]).sum(-1))
+        assert np.abs(lse_np[b, j] - ref_lse).max() <= 2e-2
+
+
+@pytest.mark.parametrize("name", ["gpt1p3b", "gpt7b_tp2", "gpt13b", "llama7b"])
+def test_one_full_size_layer_of_each_workload(name):
+    w = dict(SI.WORKLOADS[name], n_layers=1, n_mb=1)
+    gcfg, ocfg = U.make_cfgs(w)
+    params = [SI.draw_layer_params(w, 0, perturb_vectors=True)]
+    xs, dys = [SI.draw_activation(w, "x", 0)], [SI.draw_activation(w, "dy", 0)]
+    st = P.Stage(gcfg)
+    U.load_params(st, params)
+    ys, dxs = U.run_gpu(st, xs, dys)
+    o_ys, o_dxs, o_grads = U.run_oracle(ocfg, params, xs, dys, np.float32)
+    wa, wg = U.compare_stage(st, params, ys, dxs, o_ys, o_dxs, o_grads)
+    print("%s: worst activation err %.3e, worst gradient err %.3e" % (name, wa, wg))
+
+
+def test_benchmark_iteration_properties():
+    """The complete gpt7b_tp2 iteration (4 layers, 8 micro-batches) as bench.py launches it."""
+    w = SI.WORKLOADS["gpt7b_tp2"]
+    gcfg, _ = U.make_cfgs(w)
+    st = P.Stage(gcfg)
+    torch.manual_seed(1)
+    st.params.normal_(0.0, 0.02)
+    for l in range(w["n_layers"]):
+        st.param_view(l, "ln1_g").fill_(1.0)
+        st.param_view(l, "ln2_g").fill_(1.0)
+    T, K = w["mb"] * w["seq"], w["n_mb"]
+    xs = [torch.randn(T, w["hidden"], device="cuda").to(torch.bfloat16) for _ in range(K)]
+    dys = [torch.randn(T, w["hidden"], device="cuda").to(torch.bfloat16) for _ in range(K)]
+    y, dx = torch.empty_like(xs[0]), torch.empty_like(xs[0])
+
+    def iteration(restart=True):
+        if restart:
+            st.zero_grads()
+        for m in range(K):
+            st.forward(0, xs[m], y)
+            st.backward(0, dys[m], dx)
+        torch.cuda.synchronize()
+
+    iteration()
+    g1, y1, dx1 = st.grads.clone(), y.clone(), dx.clone()
+    assert torch.isfinite(g1).all() and torch.isfinite(y1.float()).all() and torch.isfinite(dx1.float()).all()
+    assert float(g1.abs().max()) > 0
+    iteration()
+    assert torch.equal(g1, st.grads) and torch.equal(y1, y) and torch.equal(dx1, dx)   # bit-reproducible
+    iteration(restart=False)                                                            # accumulate a second pass on top
+    err = ((st.grads.double() - 2 * g1.double()).norm() / (2 * g1.double()).norm()).item()
+    assert err <= 1e-6, err
