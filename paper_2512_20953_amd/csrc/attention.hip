@@ -12,7 +12,8 @@
 //     operand's 8 slots; the other operand is fetched from LDS in the matching
 //     slot order with the transposing LDS read.
 // Tiles of 64 rows of K, V (or Q, dO) are staged through LDS by direct
-// global->LDS loads, double buffered.
+// global->LDS loads into a 4-slot ring; loads run 3 tiles ahead and are waited
+// for by count, with one block barrier per tile.
 //
 // Backward is two deterministic kernels (no atomics): one block per 128 keys
 // accumulates dK and dV over the query tiles at or after it, one block per 128
@@ -139,25 +140,21 @@ __device__ __forceinline__ void fwd_tile(const char* __restrict__ cK, const char
 }
 
 template <int D>
-__device__ __forceinline__ void fwd_step(bool prefetch, const bf16* gK, const bf16* gV, const uint32_t* off, char* __restrict__ nK,
+__device__ __forceinline__ void fwd_step(const bf16* gK, const bf16* gV, const uint32_t* off, char* __restrict__ nK,
                                          char* __restrict__ nV, const char* __restrict__ cK, const char* __restrict__ cV,
                                          FwdState<D>& st, int k0, int q, int qw0, float sc2, int wave, int lane) {
-  if (prefetch) {
-    issue_tile<D>(gK, off, nK, wave);
-    issue_tile<D>(gV, off, nV, wave);
-  }
+  issue_tile<D>(gK, off, nK, wave);
+  issue_tile<D>(gV, off, nV, wave);
   fwd_tile<D>(cK, cV, st, k0, q, qw0, sc2, lane);
 }
 
 template <int D>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
                                                        int S, int nh, float sc2) {
-  constexpr int TILEB = 64 * 2 * D;
-  __shared__ __attribute__((aligned(1024))) char sK0[TILEB];
-  __shared__ __attribute__((aligned(1024))) char sK1[TILEB];
-  __shared__ __attribute__((aligned(1024))) char sV0[TILEB];
-  __shared__ __attribute__((aligned(1024))) char sV1[TILEB];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
+  constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, LPS = 2 * (D / 32);  // ring slot = K tile then V tile
+  __shared__ __attribute__((aligned(1024))) char ring[4 * STAGE];
+  const int lane = threadIdx.x & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: LDS bases stay scalar
   const int nbh = gridDim.x / (S / 128);
   const int bh = blockIdx.x % nbh;
   const int qb = S / 128 - 1 - blockIdx.x / nbh;  // heaviest query blocks first
@@ -182,24 +179,28 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ 
 #pragma unroll
   for (int i = 0; i < D / 32; i++) off[i] = tile_src_offset<D>(wave + 4 * i, lane, ld);
 
-  const int ntile = 2 * qb + 2;  // key tiles of 64 up to and including the diagonal; even
-  issue_tile<D>(kp, off, sK0, wave);
-  issue_tile<D>(vp, off, sV0, wave);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
+  // key tiles of 64 up to and including the diagonal.  Tile t lives in ring slot t % 4; the tile
+  // loaded during step j is min(j + 3, last): past the end the last tile is fetched again into a dead
+  // slot, which keeps the number of loads in flight uniform for the counted wait.
+  const int ntile = 2 * qb + 2, last = ntile - 1;
   const size_t step = (size_t)64 * ld;
-  for (int j = 0; j < ntile; j += 2) {
-    kp += step;
-    vp += step;
-    fwd_step<D>(true, kp, vp, off, sK1, sV1, sK0, sV0, st, j * 64, q, qw0, sc2, wave, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    kp += step;
-    vp += step;
-    fwd_step<D>(j + 2 < ntile, kp, vp, off, sK0, sV0, sK1, sV1, st, (j + 1) * 64, q, qw0, sc2, wave, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+#pragma unroll
+  for (int t = 0; t < 3; t++) {
+    const size_t o = (size_t)min(t, last) * step;
+    issue_tile<D>(kp + o, off, ring + t * STAGE, wave);
+    issue_tile<D>(vp + o, off, ring + t * STAGE + TILEB, wave);
   }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+  __builtin_amdgcn_s_barrier();
+  for (int j = 0; j < ntile; j++) {
+    const size_t o = (size_t)min(j + 3, last) * step;
+    char* fill = ring + ((j + 3) & 3) * STAGE;
+    const char* cur = ring + (j & 3) * STAGE;
+    fwd_step<D>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+    __builtin_amdgcn_s_barrier();
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant tail loads
 
   const float l = st.l + __shfl_xor(st.l, 32, 64);
   const float inv = 1.f / l;
@@ -283,13 +284,11 @@ __device__ __forceinline__ void dq_tile(const char* __restrict__ cK, const char*
 }
 
 template <int D>
-__device__ __forceinline__ void dq_step(bool prefetch, const bf16* gK, const bf16* gV, const uint32_t* off, char* __restrict__ nK,
+__device__ __forceinline__ void dq_step(const bf16* gK, const bf16* gV, const uint32_t* off, char* __restrict__ nK,
                                         char* __restrict__ nV, const char* __restrict__ cK, const char* __restrict__ cV,
                                         DqState<D>& st, int k0, int q, int qw0, float sc2, int wave, int lane) {
-  if (prefetch) {
-    issue_tile<D>(gK, off, nK, wave);
-    issue_tile<D>(gV, off, nV, wave);
-  }
+  issue_tile<D>(gK, off, nK, wave);
+  issue_tile<D>(gV, off, nV, wave);
   dq_tile<D>(cK, cV, st, k0, q, qw0, sc2, lane);
 }
 
@@ -297,12 +296,10 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
                                                       const float* __restrict__ lse, const float* __restrict__ delta,
                                                       bf16* __restrict__ dqkv, int S, int nh, float sc2, float scale) {
-  constexpr int TILEB = 64 * 2 * D;
-  __shared__ __attribute__((aligned(1024))) char sK0[TILEB];
-  __shared__ __attribute__((aligned(1024))) char sK1[TILEB];
-  __shared__ __attribute__((aligned(1024))) char sV0[TILEB];
-  __shared__ __attribute__((aligned(1024))) char sV1[TILEB];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
+  constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, LPS = 2 * (D / 32);  // ring slot = K tile then V tile
+  __shared__ __attribute__((aligned(1024))) char ring[4 * STAGE];
+  const int lane = threadIdx.x & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: LDS bases stay scalar
   const int nbh = gridDim.x / (S / 128);
   const int bh = blockIdx.x % nbh;
   const int qb = S / 128 - 1 - blockIdx.x / nbh;
@@ -331,24 +328,28 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(const bf16* __restrict__ q
 #pragma unroll
   for (int i = 0; i < D / 32; i++) off[i] = tile_src_offset<D>(wave + 4 * i, lane, ld);
 
-  const int ntile = 2 * qb + 2;
-  issue_tile<D>(kp, off, sK0, wave);
-  issue_tile<D>(vp, off, sV0, wave);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
+  // key tiles of 64 up to and including the diagonal.  Tile t lives in ring slot t % 4; the tile
+  // loaded during step j is min(j + 3, last): past the end the last tile is fetched again into a dead
+  // slot, which keeps the number of loads in flight uniform for the counted wait.
+  const int ntile = 2 * qb + 2, last = ntile - 1;
   const size_t step = (size_t)64 * ld;
-  for (int j = 0; j < ntile; j += 2) {
-    kp += step;
-    vp += step;
-    dq_step<D>(true, kp, vp, off, sK1, sV1, sK0, sV0, st, j * 64, q, qw0, sc2, wave, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    kp += step;
-    vp += step;
-    dq_step<D>(j + 2 < ntile, kp, vp, off, sK0, sV0, sK1, sV1, st, (j + 1) * 64, q, qw0, sc2, wave, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+#pragma unroll
+  for (int t = 0; t < 3; t++) {
+    const size_t o = (size_t)min(t, last) * step;
+    issue_tile<D>(kp + o, off, ring + t * STAGE, wave);
+    issue_tile<D>(vp + o, off, ring + t * STAGE + TILEB, wave);
   }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+  __builtin_amdgcn_s_barrier();
+  for (int j = 0; j < ntile; j++) {
+    const size_t o = (size_t)min(j + 3, last) * step;
+    char* fill = ring + ((j + 3) & 3) * STAGE;
+    const char* cur = ring + (j & 3) * STAGE;
+    dq_step<D>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+    __builtin_amdgcn_s_barrier();
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant tail loads
 
   bf16* out = dqkv + ((size_t)b * S + q) * ld + head * D;
 #pragma unroll
@@ -371,7 +372,7 @@ struct DkvState {
 
 template <int D>
 __device__ __forceinline__ void dkv_tile(const char* __restrict__ cQ, const char* __restrict__ cO, DkvState<D>& st,
-                                         const float* __restrict__ lse_row, const float* __restrict__ delta_row, int q0, int key,
+                                         const float* __restrict__ lse_tile, const float* __restrict__ delta_tile, int q0, int key,
                                          int kw0, float sc2, int lane) {
   const int hf = lane >> 5;
   if (q0 + 63 < kw0) return;  // every query of this tile is before every key of the wave
@@ -390,9 +391,9 @@ __device__ __forceinline__ void dkv_tile(const char* __restrict__ cQ, const char
     // lane holds queries q0 + t*32 + 8g + 4hf + i of its key
 #pragma unroll
     for (int g = 0; g < 4; g++) {
-      const int qq = q0 + t * 32 + 8 * g + 4 * hf;
-      const f32x4 l4 = *(const f32x4*)(lse_row + qq);
-      const f32x4 d4 = *(const f32x4*)(delta_row + qq);
+      const int ql = t * 32 + 8 * g + 4 * hf, qq = q0 + ql;
+      const f32x4 l4 = *(const f32x4*)(lse_tile + ql);
+      const f32x4 d4 = *(const f32x4*)(delta_tile + ql);
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         const int r = 4 * g + i;
@@ -415,28 +416,36 @@ __device__ __forceinline__ void dkv_tile(const char* __restrict__ cQ, const char
   }
 }
 
+// ring slot of the dK/dV kernel: Q tile, dO tile, then 64 log-sum-exps, 64 deltas and 512 spare bytes
 template <int D>
-__device__ __forceinline__ void dkv_step(bool prefetch, const bf16* gQ, const bf16* gO, const uint32_t* offq, const uint32_t* offo,
-                                         char* __restrict__ nQ, char* __restrict__ nO, const char* __restrict__ cQ,
-                                         const char* __restrict__ cO, DkvState<D>& st, const float* lse_row, const float* delta_row,
+__device__ __forceinline__ void dkv_issue(const bf16* gQ, const bf16* gO, const float* gL, const float* gD, const uint32_t* offq,
+                                          const uint32_t* offo, char* __restrict__ slot, int wave, int lane) {
+  constexpr int TILEB = 64 * 2 * D;
+  issue_tile<D>(gQ, offq, slot, wave);
+  issue_tile<D>(gO, offo, slot + TILEB, wave);
+  // one 4-byte load per lane: waves 0 and 1 bring the statistics, waves 2 and 3 repeat them into the
+  // spare bytes so that every wave has the same number of loads in flight
+  const float* src = ((wave & 1) ? gD : gL) + lane;
+  __builtin_amdgcn_global_load_lds(src, AH_LDS(slot + 2 * TILEB + wave * 256), 4, 0, 0);
+}
+
+template <int D>
+__device__ __forceinline__ void dkv_step(const bf16* gQ, const bf16* gO, const float* gL, const float* gD, const uint32_t* offq,
+                                         const uint32_t* offo, char* __restrict__ fill, const char* __restrict__ cur, DkvState<D>& st,
                                          int q0, int key, int kw0, float sc2, int wave, int lane) {
-  if (prefetch) {
-    issue_tile<D>(gQ, offq, nQ, wave);
-    issue_tile<D>(gO, offo, nO, wave);
-  }
-  dkv_tile<D>(cQ, cO, st, lse_row, delta_row, q0, key, kw0, sc2, lane);
+  constexpr int TILEB = 64 * 2 * D;
+  dkv_issue<D>(gQ, gO, gL, gD, offq, offo, fill, wave, lane);
+  dkv_tile<D>(cur, cur + TILEB, st, (const float*)(cur + 2 * TILEB), (const float*)(cur + 2 * TILEB + 256), q0, key, kw0, sc2, lane);
 }
 
 template <int D>
 __global__ __launch_bounds__(256) void attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
                                                        const float* __restrict__ lse, const float* __restrict__ delta,
                                                        bf16* __restrict__ dqkv, int S, int nh, float sc2, float scale) {
-  constexpr int TILEB = 64 * 2 * D;
-  __shared__ __attribute__((aligned(1024))) char sQ0[TILEB];
-  __shared__ __attribute__((aligned(1024))) char sQ1[TILEB];
-  __shared__ __attribute__((aligned(1024))) char sO0[TILEB];
-  __shared__ __attribute__((aligned(1024))) char sO1[TILEB];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5;
+  constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB + 1024, LPS = 2 * (D / 32) + 1;
+  __shared__ __attribute__((aligned(1024))) char ring[4 * STAGE];
+  const int lane = threadIdx.x & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: LDS bases stay scalar
   const int nbh = gridDim.x / (S / 128);
   const int bh = blockIdx.x % nbh;
   const int kb = blockIdx.x / nbh;  // key block 0 sees every query tile: heaviest first
@@ -468,27 +477,29 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(const bf16* __restrict__ 
     offo[i] = tile_src_offset<D>(wave + 4 * i, lane, ldo);
   }
 
-  const int j0 = 2 * kb, ntile = S / 64 - j0;  // query tiles of 64 from the diagonal on; even
+  // query tiles of 64 from the diagonal on.  Tile t lives in ring slot t % 4; past the end the last
+  // tile is fetched again into a dead slot (uniform number of loads in flight for the counted wait).
+  const int j0 = 2 * kb, ntile = S / 64 - j0, last = ntile - 1;
   qp += (size_t)j0 * 64 * ld;
   dop += (size_t)j0 * 64 * ldo;
-  issue_tile<D>(qp, offq, sQ0, wave);
-  issue_tile<D>(dop, offo, sO0, wave);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
+  lse_row += j0 * 64;
+  delta_row += j0 * 64;
   const size_t stepq = (size_t)64 * ld, stepo = (size_t)64 * ldo;
-  for (int j = 0; j < ntile; j += 2) {
-    qp += stepq;
-    dop += stepo;
-    dkv_step<D>(true, qp, dop, offq, offo, sQ1, sO1, sQ0, sO0, st, lse_row, delta_row, (j0 + j) * 64, key, kw0, sc2, wave, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    qp += stepq;
-    dop += stepo;
-    dkv_step<D>(j + 2 < ntile, qp, dop, offq, offo, sQ0, sO0, sQ1, sO1, st, lse_row, delta_row, (j0 + j + 1) * 64, key, kw0, sc2,
-                wave, lane);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+#pragma unroll
+  for (int t = 0; t < 3; t++) {
+    const int tt = min(t, last);
+    dkv_issue<D>(qp + tt * stepq, dop + tt * stepo, lse_row + tt * 64, delta_row + tt * 64, offq, offo, ring + t * STAGE, wave, lane);
   }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+  __builtin_amdgcn_s_barrier();
+  for (int j = 0; j < ntile; j++) {
+    const int tf = min(j + 3, last);
+    dkv_step<D>(qp + tf * stepq, dop + tf * stepo, lse_row + tf * 64, delta_row + tf * 64, offq, offo, ring + ((j + 3) & 3) * STAGE,
+                ring + (j & 3) * STAGE, st, (j0 + j) * 64, key, kw0, sc2, wave, lane);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+    __builtin_amdgcn_s_barrier();
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant tail loads
 
   bf16* outk = dqkv + ((size_t)b * S + key) * ld + nh * D + head * D;
   bf16* outv = outk + nh * D;

@@ -37,21 +37,23 @@ __device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b) {
 __device__ __forceinline__ float bf2f(bf16 v) { return (float)v; }
 __device__ __forceinline__ bf16 f2bf(float v) { return (bf16)v; }  // round to nearest even
 
-__device__ __forceinline__ float fast_tanh(float x) {
-  // tanh(x) = 1 - 2 / (exp(2x) + 1); exp overflow gives +inf -> 1, underflow gives 0 -> -1
-  float e = __expf(2.0f * x);
-  return 1.0f - 2.0f / (e + 1.0f);
+// tanh-form GeLU written through the logistic function: with z = kappa (u + 0.044715 u^3),
+// 0.5 (1 + tanh z) = sigma(2 z), so gelu(u) = u sigma(2z) and
+// gelu'(u) = sigma(2z) (1 + 2 u (1 - sigma(2z)) kappa (1 + 0.134145 u^2)).
+// sigma uses the hardware exp2 and reciprocal (1 ulp each); exp2 overflow gives sigma = 0 exactly.
+#define AH_KAPPA 0.7978845608028654f
+__device__ __forceinline__ float sigmoid2z(float u) {
+  const float z2 = (2.0f * AH_KAPPA) * __builtin_fmaf(0.044715f * u * u, u, u);
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z2));
+}
+__device__ __forceinline__ float gelu_f(float u) { return u * sigmoid2z(u); }
+__device__ __forceinline__ float gelu_grad_f(float u) {
+  const float s = sigmoid2z(u);
+  return s * __builtin_fmaf(2.0f * u * (1.0f - s), AH_KAPPA * __builtin_fmaf(0.134145f, u * u, 1.0f), 1.0f);
 }
 
-#define AH_KAPPA 0.7978845608028654f
-__device__ __forceinline__ float gelu_f(float u) {
-  float t = fast_tanh(AH_KAPPA * (u + 0.044715f * u * u * u));
-  return 0.5f * u * (1.0f + t);
-}
-__device__ __forceinline__ float gelu_grad_f(float u) {
-  float t = fast_tanh(AH_KAPPA * (u + 0.044715f * u * u * u));
-  return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * AH_KAPPA * (1.0f + 0.134145f * u * u);
-}
+// s_waitcnt immediate (gfx9 encoding): vmcnt = n (6 bits, split), lgkmcnt = 0, expcnt untouched
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

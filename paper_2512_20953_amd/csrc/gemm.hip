@@ -112,9 +112,6 @@ __device__ __forceinline__ void mma_step(const Frags<BM, BN, WGM, WGN, AKS, BKS>
       acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[tn], f.a[tm], acc[tm][tn], 0, 0, 0);
 }
 
-// s_waitcnt immediate: vmcnt = n (6 bits, split), lgkmcnt = 0, expcnt untouched
-constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
-
 // One stage (32 of k) of the pipeline.  On entry f0 holds the fragments of
 // k-step 0 of the current stage (cA, cB).  Starts the loads of the stage three
 // ahead into the ring slot that the previous stage just vacated (fA, fB),
@@ -169,8 +166,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   // flight on one XCD reuse the same operand panels in its L2.
   const int tiles_m = g.M / BM, tiles_n = g.N / BN, ntiles = tiles_m * tiles_n;
   int logical = blockIdx.x;
-  if ((ntiles & 7) == 0) logical = (blockIdx.x & 7) * (ntiles >> 3) + (blockIdx.x >> 3);
-  constexpr int GROUP = 8;
+  if ((ntiles & 7) == 0 && g.xcd_remap) logical = (blockIdx.x & 7) * (ntiles >> 3) + (blockIdx.x >> 3);
+  const int GROUP = g.group;
   const int per_group = GROUP * tiles_n;
   const int gid = logical / per_group;
   const int first_m = gid * GROUP;
@@ -369,7 +366,11 @@ hipError_t run_tile(int t, const GemmArgs& a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, hipStream_t s) {
+hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in, hipStream_t s) {
+  GemmArgs a = a_in;
+  static int grp = -1, remap = -1;
+  if (grp < 0) { grp = getenv("AH_GEMM_GROUP") ? atoi(getenv("AH_GEMM_GROUP")) : 8; remap = getenv("AH_GEMM_NOREMAP") ? 0 : 1; }
+  a.group = grp; a.xcd_remap = remap;
   if (!gemm_shape_ok(a.M, a.N, a.K)) return hipErrorInvalidValue;
   const int t = pick_tile(a.M, a.N);
   if (t < 0) return hipErrorInvalidValue;

@@ -25,6 +25,7 @@ struct GemmArgs {
   int lda, ldb, ldc, ld_aux;
   int M, N, K;
   int beta;
+  int group, xcd_remap;  // tile rasterisation (set by launch_gemm)
 };
 
 // M, N, K multiples of 128, all leading dimensions multiples of 8.

@@ -85,15 +85,18 @@ __global__ __launch_bounds__(NT) void norm_fwd_kernel(const bf16* __restrict__ x
 }
 
 // ---------------------------------------------------------------- norm backward
-// Block b handles rows [b*rpb, (b+1)*rpb); a thread keeps its columns for all of
-// them, so the three column sums accumulate in registers and leave the block once.
+// Block b handles rows [b*rpb, (b+1)*rpb); a thread keeps its columns for all of them, so the
+// three column sums accumulate in registers and leave the block once.  Rows go through in
+// batches of RB (4 for hidden <= 4096): their loads are all in flight together and one block reduction serves the batch.
 template <bool RMS, int MAXC>
 __global__ __launch_bounds__(NT) void norm_bwd_kernel(const bf16* __restrict__ da, const bf16* __restrict__ x,
                                                       const float* __restrict__ stats, const bf16* __restrict__ gamma,
                                                       const bf16* __restrict__ dres, bf16* __restrict__ dx,
                                                       float* __restrict__ part, int T, int h, int rpb) {
-  __shared__ float red[8];
+  constexpr int RB = MAXC <= 2 ? 4 : (MAXC <= 4 ? 2 : 1);  // rows per batch, bounded by the register file
+  __shared__ float red[4][2 * RB];
   const int nchunk = h >> 3, nblk = gridDim.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float gam[MAXC][8], s_g[MAXC][8], s_b[MAXC][8], s_r[MAXC][8];
 #pragma unroll
   for (int i = 0; i < MAXC; i++) {
@@ -105,42 +108,81 @@ __global__ __launch_bounds__(NT) void norm_bwd_kernel(const bf16* __restrict__ d
     }
   }
   const int r0 = blockIdx.x * rpb, r1 = min(T, r0 + rpb);
-  for (int row = r0; row < r1; row++) {
-    const float mean = stats[2 * row], rstd = stats[2 * row + 1];
-    float xh[MAXC][8], w[MAXC][8];
-    float sw = 0.f, swx = 0.f;
+  for (int rb = r0; rb < r1; rb += RB) {
+    float xh[RB][MAXC][8], w[RB][MAXC][8], rstd[RB], sums[2 * RB];
+    bf16x8 tx[RB][MAXC], td[RB][MAXC];
+    // all loads of the batch first, so that they are in flight together
 #pragma unroll
-    for (int i = 0; i < MAXC; i++) {
-      const int c = threadIdx.x + i * NT;
-      if (c < nchunk) {
-        bf16x8 tx = *(const bf16x8*)(x + (size_t)row * h + c * 8);
-        bf16x8 td = *(const bf16x8*)(da + (size_t)row * h + c * 8);
+    for (int k = 0; k < RB; k++) {
+      const int row = min(rb + k, r1 - 1);   // a short last batch repeats its last row; the copy is not used
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-          const float d = bf2f(td[j]);
-          xh[i][j] = (bf2f(tx[j]) - mean) * rstd;
-          w[i][j] = d * gam[i][j];
-          sw += w[i][j];
-          swx += w[i][j] * xh[i][j];
-          s_g[i][j] += d * xh[i][j];
-          s_b[i][j] += d;
+      for (int i = 0; i < MAXC; i++) {
+        const int c = threadIdx.x + i * NT;
+        if (c < nchunk) {
+          tx[k][i] = *(const bf16x8*)(x + (size_t)row * h + c * 8);
+          td[k][i] = *(const bf16x8*)(da + (size_t)row * h + c * 8);
         }
       }
     }
-    if (RMS) { swx = block_sum(swx, red); sw = 0.f; } else block_sum2(sw, swx, red);
-    const float c1 = sw / h, c2 = swx / h;
 #pragma unroll
-    for (int i = 0; i < MAXC; i++) {
-      const int c = threadIdx.x + i * NT;
-      if (c < nchunk) {
-        bf16x8 tr = *(const bf16x8*)(dres + (size_t)row * h + c * 8), o;
+    for (int k = 0; k < RB; k++) {
+      const int row = min(rb + k, r1 - 1);
+      const float mean = stats[2 * row];
+      rstd[k] = stats[2 * row + 1];
+      float sw = 0.f, swx = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-          const float r = bf2f(tr[j]);
-          s_r[i][j] += r;
-          o[j] = f2bf(r + rstd * (w[i][j] - c1 - xh[i][j] * c2));
+      for (int i = 0; i < MAXC; i++) {
+        const int c = threadIdx.x + i * NT;
+        if (c < nchunk) {
+#pragma unroll
+          for (int j = 0; j < 8; j++) {
+            const float d = bf2f(td[k][i][j]);
+            xh[k][i][j] = (bf2f(tx[k][i][j]) - mean) * rstd[k];
+            w[k][i][j] = d * gam[i][j];
+            sw += w[k][i][j];
+            swx += w[k][i][j] * xh[k][i][j];
+            if (rb + k < r1) { s_g[i][j] += d * xh[k][i][j]; s_b[i][j] += d; }
+          }
         }
-        *(bf16x8*)(dx + (size_t)row * h + c * 8) = o;
+      }
+      sums[2 * k] = wave_sum(sw);
+      sums[2 * k + 1] = wave_sum(swx);
+    }
+    bf16x8 tr[RB][MAXC];
+#pragma unroll
+    for (int k = 0; k < RB; k++) {
+      const int row = min(rb + k, r1 - 1);
+#pragma unroll
+      for (int i = 0; i < MAXC; i++) {
+        const int c = threadIdx.x + i * NT;
+        if (c < nchunk) tr[k][i] = *(const bf16x8*)(dres + (size_t)row * h + c * 8);
+      }
+    }
+    __syncthreads();  // red may still be read from the previous batch
+    if (lane == 0) {
+#pragma unroll
+      for (int k = 0; k < 2 * RB; k++) red[wave][k] = sums[k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < RB; k++) {
+      if (rb + k >= r1) break;
+      const int row = rb + k;
+      const float c1 = RMS ? 0.f : (red[0][2 * k] + red[1][2 * k] + red[2][2 * k] + red[3][2 * k]) / h;
+      const float c2 = (red[0][2 * k + 1] + red[1][2 * k + 1] + red[2][2 * k + 1] + red[3][2 * k + 1]) / h;
+#pragma unroll
+      for (int i = 0; i < MAXC; i++) {
+        const int c = threadIdx.x + i * NT;
+        if (c < nchunk) {
+          bf16x8 o;
+#pragma unroll
+          for (int j = 0; j < 8; j++) {
+            const float r = bf2f(tr[k][i][j]);
+            s_r[i][j] += r;
+            o[j] = f2bf(r + rstd[k] * (w[k][i][j] - c1 - xh[k][i][j] * c2));
+          }
+          *(bf16x8*)(dx + (size_t)row * h + c * 8) = o;
+        }
       }
     }
   }
@@ -189,24 +231,30 @@ __global__ __launch_bounds__(NT) void colsum_partial_kernel(const bf16* __restri
   }
 }
 
-// g[c] = beta * g[c] + sum_b part[b][c] for up to three (part, g) pairs that share n and nblk
+// g[c] = beta * g[c] + sum_b part[b][c] for up to three (part, g) pairs that share n and nblk.
+// A block takes 64 columns; its four waves each sum a quarter of the partial rows.
 struct FinishArgs { const float* part[3]; float* g[3]; };
 __global__ __launch_bounds__(NT) void colsum_finish_kernel(FinishArgs a, int nblk, int n, int beta) {
-  const int c = blockIdx.x * NT + threadIdx.x;
-  if (c >= n) return;
+  __shared__ float red[3][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
   const float* part = a.part[blockIdx.y];
-  float* g = a.g[blockIdx.y];
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  int b = 0;
-  for (; b + 4 <= nblk; b += 4) {
-    s0 += part[(size_t)b * n + c];
-    s1 += part[(size_t)(b + 1) * n + c];
-    s2 += part[(size_t)(b + 2) * n + c];
-    s3 += part[(size_t)(b + 3) * n + c];
+  float s0 = 0.f, s1 = 0.f;
+  if (c < n) {
+    int b = wave;
+    for (; b + 4 < nblk; b += 8) {
+      s0 += part[(size_t)b * n + c];
+      s1 += part[(size_t)(b + 4) * n + c];
+    }
+    if (b < nblk) s0 += part[(size_t)b * n + c];
   }
-  for (; b < nblk; b++) s0 += part[(size_t)b * n + c];
-  const float s = (s0 + s1) + (s2 + s3);
-  g[c] = beta ? g[c] + s : s;
+  if (wave > 0) red[wave - 1][lane] = s0 + s1;
+  __syncthreads();
+  if (wave == 0 && c < n) {
+    const float s = (s0 + s1) + red[0][lane] + red[1][lane] + red[2][lane];
+    float* g = a.g[blockIdx.y];
+    g[c] = beta ? g[c] + s : s;
+  }
 }
 
 // ---------------------------------------------------------------- rotary embedding
@@ -325,13 +373,13 @@ hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float*
 
 hipError_t launch_colsum_finish(const float* part, int nblk, int n, float* g, int beta, hipStream_t s) {
   FinishArgs a = {{part, nullptr, nullptr}, {g, nullptr, nullptr}};
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + NT - 1) / NT, 1), dim3(NT), 0, s, a, nblk, n, beta);
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + 63) / 64, 1), dim3(NT), 0, s, a, nblk, n, beta);
   return hipGetLastError();
 }
 
 hipError_t launch_colsum_finish3(const float* part, int nblk, int n, float* g0, float* g1, float* g2, int beta, hipStream_t s) {
   FinishArgs a = {{part, part + (size_t)nblk * n, part + (size_t)2 * nblk * n}, {g0, g1, g2}};
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + NT - 1) / NT, 3), dim3(NT), 0, s, a, nblk, n, beta);
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + 63) / 64, 3), dim3(NT), 0, s, a, nblk, n, beta);
   return hipGetLastError();
 }
 
