@@ -26,6 +26,7 @@ namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
+constexpr int NSLOT = 2;  // ring slots of the forward and dQ kernels (two blocks share a CU)
 
 // LDS tile [64 rows][D] bf16.  16-byte piece p of row r is stored at piece
 // swz(r, p): conflict-free both for 16-byte reads down a column of pieces and
@@ -149,10 +150,10 @@ __device__ __forceinline__ void fwd_step(const bf16* gK, const bf16* gV, const u
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
                                                        int S, int nh, float sc2) {
   constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, LPS = 2 * (D / 32);  // ring slot = K tile then V tile
-  __shared__ __attribute__((aligned(1024))) char ring[4 * STAGE];
+  __shared__ __attribute__((aligned(1024))) char ring[NSLOT * STAGE];
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: LDS bases stay scalar
   const int nbh = gridDim.x / (S / 128);
@@ -179,25 +180,25 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ 
 #pragma unroll
   for (int i = 0; i < D / 32; i++) off[i] = tile_src_offset<D>(wave + 4 * i, lane, ld);
 
-  // key tiles of 64 up to and including the diagonal.  Tile t lives in ring slot t % 4; the tile
-  // loaded during step j is min(j + 3, last): past the end the last tile is fetched again into a dead
+  // key tiles of 64 up to and including the diagonal.  Tile t lives in ring slot t % NSLOT; the tile
+  // loaded during step j is min(j + NSLOT - 1, last): past the end the last tile is fetched again into a dead
   // slot, which keeps the number of loads in flight uniform for the counted wait.
   const int ntile = 2 * qb + 2, last = ntile - 1;
   const size_t step = (size_t)64 * ld;
 #pragma unroll
-  for (int t = 0; t < 3; t++) {
+  for (int t = 0; t < NSLOT - 1; t++) {
     const size_t o = (size_t)min(t, last) * step;
     issue_tile<D>(kp + o, off, ring + t * STAGE, wave);
     issue_tile<D>(vp + o, off, ring + t * STAGE + TILEB, wave);
   }
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
   __builtin_amdgcn_s_barrier();
   for (int j = 0; j < ntile; j++) {
-    const size_t o = (size_t)min(j + 3, last) * step;
-    char* fill = ring + ((j + 3) & 3) * STAGE;
-    const char* cur = ring + (j & 3) * STAGE;
+    const size_t o = (size_t)min(j + NSLOT - 1, last) * step;
+    char* fill = ring + ((j + NSLOT - 1) & (NSLOT - 1)) * STAGE;
+    const char* cur = ring + (j & (NSLOT - 1)) * STAGE;
     fwd_step<D>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
     __builtin_amdgcn_s_barrier();
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant tail loads
@@ -293,11 +294,11 @@ __device__ __forceinline__ void dq_step(const bf16* gK, const bf16* gV, const ui
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
+__global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
                                                       const float* __restrict__ lse, const float* __restrict__ delta,
                                                       bf16* __restrict__ dqkv, int S, int nh, float sc2, float scale) {
   constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, LPS = 2 * (D / 32);  // ring slot = K tile then V tile
-  __shared__ __attribute__((aligned(1024))) char ring[4 * STAGE];
+  __shared__ __attribute__((aligned(1024))) char ring[NSLOT * STAGE];
   const int lane = threadIdx.x & 63, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: LDS bases stay scalar
   const int nbh = gridDim.x / (S / 128);
@@ -328,25 +329,25 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(const bf16* __restrict__ q
 #pragma unroll
   for (int i = 0; i < D / 32; i++) off[i] = tile_src_offset<D>(wave + 4 * i, lane, ld);
 
-  // key tiles of 64 up to and including the diagonal.  Tile t lives in ring slot t % 4; the tile
-  // loaded during step j is min(j + 3, last): past the end the last tile is fetched again into a dead
+  // key tiles of 64 up to and including the diagonal.  Tile t lives in ring slot t % NSLOT; the tile
+  // loaded during step j is min(j + NSLOT - 1, last): past the end the last tile is fetched again into a dead
   // slot, which keeps the number of loads in flight uniform for the counted wait.
   const int ntile = 2 * qb + 2, last = ntile - 1;
   const size_t step = (size_t)64 * ld;
 #pragma unroll
-  for (int t = 0; t < 3; t++) {
+  for (int t = 0; t < NSLOT - 1; t++) {
     const size_t o = (size_t)min(t, last) * step;
     issue_tile<D>(kp + o, off, ring + t * STAGE, wave);
     issue_tile<D>(vp + o, off, ring + t * STAGE + TILEB, wave);
   }
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
   __builtin_amdgcn_s_barrier();
   for (int j = 0; j < ntile; j++) {
-    const size_t o = (size_t)min(j + 3, last) * step;
-    char* fill = ring + ((j + 3) & 3) * STAGE;
-    const char* cur = ring + (j & 3) * STAGE;
+    const size_t o = (size_t)min(j + NSLOT - 1, last) * step;
+    char* fill = ring + ((j + NSLOT - 1) & (NSLOT - 1)) * STAGE;
+    const char* cur = ring + (j & (NSLOT - 1)) * STAGE;
     dq_step<D>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
     __builtin_amdgcn_s_barrier();
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant tail loads
