@@ -20,3 +20,4 @@ product are measurements and have no oracle; its byte counts are checked
 against integer identities in the tests.)
 """
 from .stage_ref import *  # noqa: F401,F403
+from . import cost_ref  # noqa: F401

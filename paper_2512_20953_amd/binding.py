@@ -85,6 +85,12 @@ def _load():
     L.ah_stage_profile.argtypes = [vp, i, i, C.POINTER(_Profile)]
     L.ah_stage_trace_begin.argtypes = [vp]
     L.ah_stage_trace_end.argtypes = [vp, C.POINTER(_TraceEntry), i, C.POINTER(i)]
+    dp, ip = C.POINTER(C.c_double), C.POINTER(C.c_int)
+    L.ah_cost_layers_time.argtypes = [i, dp, i, dp]
+    L.ah_cost_pipeline_time.argtypes = [dp, i, i, dp]
+    L.ah_cost_iteration_time.argtypes = [dp, ip, i, i, C.c_double, dp]
+    L.ah_cost_idle_fractions.argtypes = [dp, i, i, dp, dp]
+    L.ah_cost_partition_layers.argtypes = [i, i, dp, dp, C.c_double, C.c_double, ip, ip, dp]
     L.ah_gemm_nn.argtypes = [vp, vp, vp, vp, i, i, i, vp]
     L.ah_gemm_nt.argtypes = [vp, vp, vp, i, i, i, vp]
     L.ah_gemm_tn.argtypes = [vp, vp, vp, i, i, i, i, vp]
@@ -216,3 +222,44 @@ def attention_fwd(qkv, o, lse, B, S, nh, d, stream=None):
 
 def attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, stream=None):
     _check(lib.ah_attention_bwd(_ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(delta), B, S, nh, d, _stream(stream)))
+
+
+# ---- cost model (include/ah_cost.h): host arrays in, numbers out
+def _darr(v):
+    return (C.c_double * len(v))(*[float(x) for x in v])
+
+
+def cost_layers_time(n, t_pow2):
+    out = C.c_double()
+    _check(lib.ah_cost_layers_time(int(n), _darr(t_pow2), len(t_pow2), C.byref(out)))
+    return out.value
+
+
+def cost_pipeline_time(t_stage, K):
+    out = C.c_double()
+    _check(lib.ah_cost_pipeline_time(_darr(t_stage), len(t_stage), int(K), C.byref(out)))
+    return out.value
+
+
+def cost_iteration_time(groups, K, t_sync):
+    flat = [t for g in groups for t in g]
+    stages = (C.c_int * len(groups))(*[len(g) for g in groups])
+    out = C.c_double()
+    _check(lib.ah_cost_iteration_time(_darr(flat), stages, len(groups), int(K), float(t_sync), C.byref(out)))
+    return out.value
+
+
+def cost_idle_fractions(t_stage, K):
+    idle = (C.c_double * len(t_stage))()
+    mean = C.c_double()
+    _check(lib.ah_cost_idle_fractions(_darr(t_stage), len(t_stage), int(K), idle, C.byref(mean)))
+    return list(idle), mean.value
+
+
+def cost_partition_layers(n_layers, t_layer, mem_bytes, fixed_per_layer, act_per_layer, in_flight):
+    P = len(t_layer)
+    l = (C.c_int * P)()
+    worst = C.c_double()
+    _check(lib.ah_cost_partition_layers(P, int(n_layers), _darr(t_layer), _darr(mem_bytes), float(fixed_per_layer),
+                                        float(act_per_layer), (C.c_int * P)(*[int(f) for f in in_flight]), l, C.byref(worst)))
+    return list(l), worst.value

@@ -153,3 +153,16 @@ def test_profile_reports_layers_and_bytes():
     assert prof["activation_bytes_per_layer_per_slot"] * 3 == st.sizes["activation_bytes_per_slot"]
     assert prof["param_bytes"] == st.sizes["param_bytes"] and prof["grad_bytes"] == 2 * prof["param_bytes"]
     assert prof["iteration_ms"] > 0
+
+
+def test_layer_times_add_up_as_the_profiler_assumes():
+    """Section III-D: the time of n layers is estimated from the profiles of 1, 2, 4, ... layers;
+    memory is the per-layer amount times the layer count (exact)."""
+    from paper_2512_20953_amd.profile_study import study
+    w = dict(SI.WORKLOADS["gpt1p3b"], n_mb=2)
+    prof, rows = study(w, [3], pow2=(1, 2), warmup=2, iters=5)
+    r = rows[0]
+    print("3 layers: estimated %.2f ms, measured %.2f ms" % (r["estimated_ms"], r["measured_ms"]))
+    assert abs(r["rel_err"]) < 0.10
+    assert r["activation_bytes_estimated"] == r["activation_bytes_measured"]
+    assert abs(sum(prof[3]["fwd_ms"]) - prof[3]["stage_fwd_ms"]) <= 0.1 * prof[3]["stage_fwd_ms"]
