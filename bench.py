@@ -42,7 +42,7 @@ def cpu_baseline(w, name):
         cores = os.cpu_count()
     ws = dict(w, n_layers=1, mb=1)
     nh, hl, Fl = SI.local_dims(ws)
-    cfg = R.StageCfg(ws["arch"], 1, ws["hidden"], nh, ws["head_dim"], Fl, ws["seq"], 1e-5 if ws["arch"] == "gpt" else 1e-6)
+    cfg = R.StageCfg(ws["arch"], 1, ws["hidden"], nh, ws["head_dim"], Fl, ws["seq"], 1e-6 if ws["arch"] == "llama" else 1e-5)
     rng = np.random.default_rng(0)
     params = [{n: (np.ones(s, np.float32) if k == "one" else np.zeros(s, np.float32) if k == "zero"
                    else (rng.standard_normal(s, dtype=np.float32) * np.float32(0.02)))

@@ -4,7 +4,9 @@ What is computed.  The paper balances the time t_i^j that stage i of data
 parallel group j needs for the forward and the backward pass of its layers
 (Section III-A, Eq. 1), over K micro-batches whose gradients are accumulated
 before one synchronisation.  The layers themselves are the standard pre-norm
-decoder layers of the models it trains (GPT-3, LLaMA; Section V).  Tensor
+decoder layers of the models it trains (GPT-3, LLaMA; Section V); its third
+model, BERT-Large, is read as the same pre-norm block with bidirectional
+attention (every position attends to every position of its sequence).  Tensor
 parallelism cuts the first matrix of each two-matrix block by columns and the
 second by rows (Section II-B); one shard's stage is then a network with
 heads/TP heads and FFN/TP hidden units on a residual stream of full width
@@ -31,7 +33,8 @@ __all__ = [
 
 @dataclass
 class StageCfg:
-    arch: str            # "gpt" (LayerNorm, biases, tanh-GeLU) or "llama" (RMSNorm, RoPE, SwiGLU, no biases)
+    arch: str            # "gpt" (LayerNorm, biases, tanh-GeLU), "llama" (RMSNorm, RoPE, SwiGLU, no biases)
+                         # or "bert" (the "gpt" block with bidirectional instead of causal attention)
     n_layers: int        # l_i of the layer-partition problem (Section III-C, Eq. 4)
     hidden: int          # h
     n_heads_local: int   # heads / TP
@@ -45,13 +48,21 @@ class StageCfg:
     def h_loc(self):
         return self.n_heads_local * self.head_dim
 
+    @property
+    def causal(self):
+        return self.arch != "bert"
+
+    @property
+    def gpt_block(self):
+        return self.arch in ("gpt", "bert")
+
 
 GPT_PARAMS = ["ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2"]
 LLAMA_PARAMS = ["ln1_g", "wqkv", "wo", "ln2_g", "wgu", "wd"]
 
 
 def param_names(arch):
-    return list(GPT_PARAMS if arch == "gpt" else LLAMA_PARAMS)
+    return list(GPT_PARAMS if arch in ("gpt", "bert") else LLAMA_PARAMS)
 
 
 # --------------------------------------------------------------------------
@@ -138,34 +149,35 @@ def rope_apply(t, cos, sin, sign=1.0):
 
 
 # --------------------------------------------------------------------------
-# causal self-attention, one (batch, head) at a time
+# self-attention, one (batch, head) at a time; causal: query i sees keys k <= i
 # --------------------------------------------------------------------------
-def attention_probs(q, k):
-    """Causal softmax(q k^T / sqrt(d)) for one head.  q, k: [S, d] -> P[S, S]."""
+def attention_probs(q, k, causal=True):
+    """softmax(q k^T / sqrt(d)) for one head, over the allowed keys.  q, k: [S, d] -> P[S, S]."""
     S, d = q.shape
     s = (q @ k.T) * q.dtype.type(1.0 / np.sqrt(d))
-    allowed = np.tril(np.ones((S, S), dtype=bool))
-    s = np.where(allowed, s, -np.inf)
+    if causal:
+        allowed = np.tril(np.ones((S, S), dtype=bool))
+        s = np.where(allowed, s, -np.inf)
     m = s.max(axis=-1, keepdims=True)
     e = np.exp(s - m)            # masked entries are exp(-inf) = 0 exactly
     return e / e.sum(axis=-1, keepdims=True)
 
 
-def attention_fwd(q, k, v):
+def attention_fwd(q, k, v, causal=True):
     """q, k, v: [B, nh, S, d] -> o same shape."""
     o = np.empty_like(q)
     for b in range(q.shape[0]):
         for j in range(q.shape[1]):
-            o[b, j] = attention_probs(q[b, j], k[b, j]) @ v[b, j]
+            o[b, j] = attention_probs(q[b, j], k[b, j], causal) @ v[b, j]
     return o
 
 
-def attention_bwd(q, k, v, do):
+def attention_bwd(q, k, v, do, causal=True):
     dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
     scale = q.dtype.type(1.0 / np.sqrt(q.shape[-1]))
     for b in range(q.shape[0]):
         for j in range(q.shape[1]):
-            p = attention_probs(q[b, j], k[b, j])
+            p = attention_probs(q[b, j], k[b, j], causal)
             dv[b, j] = p.T @ do[b, j]
             dp = do[b, j] @ v[b, j].T
             delta = (p * dp).sum(axis=-1, keepdims=True)
@@ -193,7 +205,7 @@ def layer_fwd(cfg, p, x):
     S, nh, d, hl = cfg.seq_len, cfg.n_heads_local, cfg.head_dim, cfg.h_loc
     B = T // S
     c = {"x": x}
-    if cfg.arch == "gpt":
+    if cfg.gpt_block:
         a, c["xhat1"], c["rstd1"] = layer_norm_fwd(x, p["ln1_g"], p["ln1_b"], cfg.norm_eps)
         qkv = a @ p["wqkv"] + p["bqkv"]
     else:
@@ -207,9 +219,9 @@ def layer_fwd(cfg, p, x):
         cos, sin = rope_tables(S, d, cfg.rope_base, x.dtype)
         q, k = rope_apply(q, cos, sin), rope_apply(k, cos, sin)
     c["q"], c["k"], c["v"] = q, k, v
-    o = _merge_heads(attention_fwd(q, k, v))
+    o = _merge_heads(attention_fwd(q, k, v, cfg.causal))
     c["o"] = o
-    if cfg.arch == "gpt":
+    if cfg.gpt_block:
         x_mid = x + o @ p["wo"] + p["bo"]
         cc, c["xhat2"], c["rstd2"] = layer_norm_fwd(x_mid, p["ln2_g"], p["ln2_b"], cfg.norm_eps)
         u = cc @ p["w1"] + p["b1"]
@@ -234,7 +246,7 @@ def layer_bwd(cfg, p, c, dy, g):
     T = dy.shape[0]
     S, nh, d, hl = cfg.seq_len, cfg.n_heads_local, cfg.head_dim, cfg.h_loc
     B = T // S
-    if cfg.arch == "gpt":
+    if cfg.gpt_block:
         g["w2"] += c["g"].T @ dy
         g["b2"] += dy.sum(axis=0)
         dg = dy @ p["w2"].T
@@ -257,17 +269,17 @@ def layer_bwd(cfg, p, c, dy, g):
         g["ln2_g"] += dgam
     dx_mid = dy + dx_ln
     g["wo"] += c["o"].T @ dx_mid
-    if cfg.arch == "gpt":
+    if cfg.gpt_block:
         g["bo"] += dx_mid.sum(axis=0)
     do = _split_heads(dx_mid @ p["wo"].T, B, S, nh, d)
-    dq, dk, dv = attention_bwd(c["q"], c["k"], c["v"], do)
+    dq, dk, dv = attention_bwd(c["q"], c["k"], c["v"], do, cfg.causal)
     if cfg.arch == "llama":
         cos, sin = rope_tables(S, d, cfg.rope_base, dy.dtype)
         dq, dk = rope_apply(dq, cos, sin, -1.0), rope_apply(dk, cos, sin, -1.0)
     dqkv = np.concatenate([_merge_heads(dq), _merge_heads(dk), _merge_heads(dv)], axis=1)
     g["wqkv"] += c["a"].T @ dqkv
     da = dqkv @ p["wqkv"].T
-    if cfg.arch == "gpt":
+    if cfg.gpt_block:
         g["bqkv"] += dqkv.sum(axis=0)
         dx_ln1, dgam, dbet = layer_norm_bwd(da, c["xhat1"], c["rstd1"], p["ln1_g"])
         g["ln1_b"] += dbet
@@ -345,7 +357,7 @@ def attn_block_partial(cfg_local, p_shard, x):
 
 def mlp_block_partial(cfg_local, p_shard, x_mid):
     """g_r @ W2_r (or m_r @ Wd_r) for one shard, from the block's input x_mid."""
-    if cfg_local.arch == "gpt":
+    if cfg_local.gpt_block:
         cc, _, _ = layer_norm_fwd(x_mid, p_shard["ln2_g"], p_shard["ln2_b"], cfg_local.norm_eps)
         return gelu_tanh(cc @ p_shard["w1"] + p_shard["b1"]) @ p_shard["w2"]
     cc, _, _ = rms_norm_fwd(x_mid, p_shard["ln2_g"], cfg_local.norm_eps)

@@ -30,7 +30,7 @@ def make_cfgs(w, max_in_flight=1, recompute=None):
                               head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
                               max_in_flight=max_in_flight, recompute=w["recompute"] if recompute is None else recompute)
     ocfg = R.StageCfg(w["arch"], w["n_layers"], w["hidden"], nh, w["head_dim"], Fl, w["seq"],
-                      1e-5 if w["arch"] == "gpt" else 1e-6, 10000.0)
+                      1e-6 if w["arch"] == "llama" else 1e-5, 10000.0)
     return gcfg, ocfg
 
 

@@ -16,7 +16,7 @@ GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
 def tiny_cfg(arch, L=2, S=6):
-    return R.StageCfg(arch, L, 16, 2, 8, 32, S, 1e-5 if arch == "gpt" else 1e-6, 10000.0)
+    return R.StageCfg(arch, L, 16, 2, 8, 32, S, 1e-6 if arch == "llama" else 1e-5, 10000.0)
 
 
 def rand_params(cfg, rng, dtype=np.float64, wstd=0.3):
@@ -47,7 +47,7 @@ def run_stage(cfg, params, xs, dys):
 
 
 # ---------------------------------------------------------------- finite differences
-@pytest.mark.parametrize("arch", ["gpt", "llama"])
+@pytest.mark.parametrize("arch", ["gpt", "llama", "bert"])
 def test_backward_matches_central_differences(arch):
     rng = np.random.default_rng(1)
     cfg = tiny_cfg(arch)
@@ -98,7 +98,8 @@ def torch_layer(arch, p, x, S, nh, d, eps, base):
     T, h = x.shape
     B = T // S
     hl = nh * d
-    if arch == "gpt":
+    gpt_block = arch in ("gpt", "bert")
+    if gpt_block:
         a = F.layer_norm(x, (h,), p["ln1_g"], p["ln1_b"], eps)
         qkv = torch.addmm(p["bqkv"], a, p["wqkv"])
     else:
@@ -114,9 +115,9 @@ def torch_layer(arch, p, x, S, nh, d, eps, base):
             z = torch.complex(t[..., : d // 2], t[..., d // 2:]) * rot
             return torch.cat([z.real, z.imag], dim=-1)
         q, k = rope(q), rope(k)
-    o = F.scaled_dot_product_attention(q, k, v, is_causal=True)
+    o = F.scaled_dot_product_attention(q, k, v, is_causal=(arch != "bert"))
     o = o.permute(0, 2, 1, 3).reshape(T, hl)
-    if arch == "gpt":
+    if gpt_block:
         xm = x + o @ p["wo"] + p["bo"]
         c = F.layer_norm(xm, (h,), p["ln2_g"], p["ln2_b"], eps)
         return xm + F.gelu(c @ p["w1"] + p["b1"], approximate="tanh") @ p["w2"] + p["b2"]
@@ -126,7 +127,7 @@ def torch_layer(arch, p, x, S, nh, d, eps, base):
     return xm + (F.silu(gate) * up) @ p["wd"]
 
 
-@pytest.mark.parametrize("arch", ["gpt", "llama"])
+@pytest.mark.parametrize("arch", ["gpt", "llama", "bert"])
 def test_stage_matches_autograd_restatement(arch):
     rng = np.random.default_rng(2)
     cfg = tiny_cfg(arch, L=3, S=10)
@@ -160,6 +161,53 @@ def test_softmax_rows_and_mask():
     assert p[0, 0] == 1.0
 
 
+def test_bidirectional_probabilities_by_brute_force():
+    # every key is allowed: plain loops over a tiny head, and scipy's softmax as a second witness
+    from scipy.special import softmax
+    rng = np.random.default_rng(31)
+    S, d = 7, 4
+    q, k = rng.standard_normal((S, d)), rng.standard_normal((S, d))
+    p = R.attention_probs(q, k, causal=False)
+    for i in range(S):
+        w = [np.exp(sum(q[i, c] * k[j, c] for c in range(d)) / np.sqrt(d)) for j in range(S)]
+        for j in range(S):
+            assert abs(p[i, j] - w[j] / sum(w)) < 1e-14
+    assert np.allclose(p, softmax(q @ k.T / 2.0, axis=-1), atol=1e-15)
+    assert (p > 0).all()
+    # the causal matrix is the same weights renormalised over the allowed prefix
+    pc = R.attention_probs(q, k, causal=True)
+    low = np.tril(p)
+    assert np.allclose(pc, low / low.sum(-1, keepdims=True), atol=1e-14)
+
+
+def test_bidirectional_stage_sees_the_whole_sequence_and_ignores_its_order():
+    rng = np.random.default_rng(32)
+    cfg = tiny_cfg("bert", L=2, S=12)
+    params = rand_params(cfg, rng)
+    B = 2
+    x = rng.standard_normal((B, cfg.seq_len, cfg.hidden))
+    y = R.stage_fwd(cfg, params, x.reshape(-1, cfg.hidden))[0].reshape(x.shape)
+    # no positional signal inside the stage: permuting the tokens of each sequence permutes the outputs
+    perm = rng.permutation(cfg.seq_len)
+    yp = R.stage_fwd(cfg, params, x[:, perm].reshape(-1, cfg.hidden))[0].reshape(x.shape)
+    assert np.allclose(yp, y[:, perm], rtol=1e-11, atol=1e-11)
+    # a change at the last position reaches the first one (it would not under the causal mask) ...
+    x2 = x.copy()
+    x2[:, -1] += rng.standard_normal(cfg.hidden)      # (a constant shift would be removed by the LayerNorm)
+    y2 = R.stage_fwd(cfg, params, x2.reshape(-1, cfg.hidden))[0].reshape(x.shape)
+    assert np.abs(y2[:, 0] - y[:, 0]).max() > 1e-6
+    # ... but never another sequence of the batch
+    x3 = x.copy()
+    x3[1] += rng.standard_normal(x3[1].shape)
+    y3 = R.stage_fwd(cfg, params, x3.reshape(-1, cfg.hidden))[0].reshape(x.shape)
+    assert np.array_equal(y3[0], y[0])
+    # and the causal stage fails the permutation property (the pin separates the two masks)
+    ccfg = tiny_cfg("gpt", L=2, S=12)
+    yc = R.stage_fwd(ccfg, params, x.reshape(-1, cfg.hidden))[0].reshape(x.shape)
+    ycp = R.stage_fwd(ccfg, params, x[:, perm].reshape(-1, cfg.hidden))[0].reshape(x.shape)
+    assert np.abs(ycp - yc[:, perm]).max() > 1e-3
+
+
 @pytest.mark.parametrize("arch", ["gpt", "llama"])
 def test_causality_is_bit_exact(arch):
     rng = np.random.default_rng(4)
@@ -176,7 +224,7 @@ def test_causality_is_bit_exact(arch):
 
 
 # ---------------------------------------------------------------- accumulation over micro-batches
-@pytest.mark.parametrize("arch", ["gpt", "llama"])
+@pytest.mark.parametrize("arch", ["gpt", "llama", "bert"])
 def test_accumulation_equals_concatenated_batch(arch):
     rng = np.random.default_rng(5)
     cfg = tiny_cfg(arch)
@@ -194,7 +242,7 @@ def test_accumulation_equals_concatenated_batch(arch):
 
 
 # ---------------------------------------------------------------- tensor-parallel partial sums
-@pytest.mark.parametrize("arch", ["gpt", "llama"])
+@pytest.mark.parametrize("arch", ["gpt", "llama", "bert"])
 def test_shard_partials_sum_to_unsharded_block(arch):
     rng = np.random.default_rng(6)
     nh, d, F, h, S, tp = 4, 8, 48, 16, 5, 2
