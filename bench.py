@@ -21,12 +21,14 @@ PEAK_HBM_GBS = 8000.0
 
 
 def model_flops_per_iter(w):
-    """2 flop per MAC, causal attention at its real half cost, backward = 2 x forward, recompute not counted."""
+    """2 flop per MAC, causal attention at its real half cost (bidirectional: all S keys), backward = 2 x forward,
+    recompute not counted."""
     tp = w["tp"]
     h, hl, F = w["hidden"], w["n_heads"] // tp * w["head_dim"], w["ffn"] // tp
     S = w["seq"]
     mlp = (6 if w["arch"] == "llama" else 4) * h * F
-    per_token_layer = 2 * h * 3 * hl + 2 * hl * h + mlp + 4 * hl * (S + 1) / 2
+    keys = S if w["arch"] == "bert" else (S + 1) / 2
+    per_token_layer = 2 * h * 3 * hl + 2 * hl * h + mlp + 4 * hl * keys
     return 3.0 * per_token_layer * w["n_layers"] * w["mb"] * S * w["n_mb"]
 
 
@@ -88,7 +90,7 @@ def main():
     for l in range(w["n_layers"]):
         for name in (["ln1_g", "ln2_g"]):
             st.param_view(l, name).fill_(1.0)
-        if w["arch"] == "gpt":
+        if w["arch"] != "llama":
             for name in ("ln1_b", "ln2_b", "bqkv", "bo", "b1", "b2"):
                 st.param_view(l, name).zero_()
     T, K = w["mb"] * w["seq"], w["n_mb"]

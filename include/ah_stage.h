@@ -53,12 +53,15 @@ typedef enum {
 } ah_status_t;
 
 typedef enum {
-  AH_ARCH_GPT = 0,  /* LayerNorm (eps 1e-5, biased variance), biases, tanh-form GeLU */
-  AH_ARCH_LLAMA = 1 /* RMSNorm, rotary embedding (pairs i, i+d/2), SwiGLU, no biases */
+  AH_ARCH_GPT = 0,   /* LayerNorm (eps 1e-5, biased variance), biases, tanh-form GeLU, causal attention */
+  AH_ARCH_LLAMA = 1, /* RMSNorm, rotary embedding (pairs i, i+d/2), SwiGLU, no biases, causal attention */
+  AH_ARCH_BERT = 2   /* the GPT block and parameter set with bidirectional attention: every position attends to
+                      * every position of its sequence (the third model of Section V, BERT-Large; full-length
+                      * sequences, no padding mask) */
 } ah_arch_t;
 
 /* Index of a parameter tensor inside a layer, in storage order.
- * GPT  : LN1_G LN1_B WQKV BQKV WO BO LN2_G LN2_B W1 B1 W2 B2   (12 tensors)
+ * GPT, BERT: LN1_G LN1_B WQKV BQKV WO BO LN2_G LN2_B W1 B1 W2 B2   (12 tensors)
  * LLAMA: LN1_G WQKV WO LN2_G W1(=gate|up, [h, 2*F_loc]) W2(=down)  (6 tensors)
  * WQKV columns are [Q | K | V], each block head-major. */
 typedef enum {
@@ -186,11 +189,12 @@ int ah_gemm_nn(const void* A, const void* B, const void* bias, void* C, int M, i
 int ah_gemm_nt(const void* A, const void* B, void* C, int M, int N, int K, void* hip_stream);
 /* C[M,N] (fp32) = beta * C + A[K,M]^T B[K,N], beta in {0, 1}.  Same constraints. */
 int ah_gemm_tn(const void* A, const void* B, float* C, int M, int N, int K, int beta, void* hip_stream);
-/* Causal attention over packed qkv[B*S, 3*nh*d] (bf16, [Q|K|V], head-major): o[B*S, nh*d] bf16, lse[B, nh, S] fp32. */
-int ah_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, void* hip_stream);
+/* Attention over packed qkv[B*S, 3*nh*d] (bf16, [Q|K|V], head-major): o[B*S, nh*d] bf16, lse[B, nh, S] fp32.
+ * causal != 0: query i attends to keys 0..i of its sequence; causal == 0: to all S keys. */
+int ah_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, int causal, void* hip_stream);
 /* Its backward: dqkv[B*S, 3*nh*d] from qkv, o, lse and do[B*S, nh*d]; `delta` is fp32 scratch [B, nh, S]. */
 int ah_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
-                     int B, int S, int nh, int d, void* hip_stream);
+                     int B, int S, int nh, int d, int causal, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -3,7 +3,7 @@ layers on one tensor-parallel shard).  Thin ctypes binding over libahstage.so;
 every step runs in the HIP kernels of that library."""
 import importlib
 
-_LAZY = ("AH_ARCH_GPT", "AH_ARCH_LLAMA", "PARAM_INDEX", "AhError", "Stage", "StageConfig", "attention_bwd",
+_LAZY = ("AH_ARCH_GPT", "AH_ARCH_LLAMA", "AH_ARCH_BERT", "PARAM_INDEX", "AhError", "Stage", "StageConfig", "attention_bwd",
          "attention_fwd", "gemm_nn", "gemm_nt", "gemm_tn", "lib", "library_path", "query_sizes", "cost_layers_time",
          "cost_pipeline_time", "cost_iteration_time", "cost_idle_fractions", "cost_partition_layers")
 

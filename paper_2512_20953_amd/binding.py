@@ -9,7 +9,8 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-AH_ARCH_GPT, AH_ARCH_LLAMA = 0, 1
+AH_ARCH_GPT, AH_ARCH_LLAMA, AH_ARCH_BERT = 0, 1, 2
+_ARCH = {"gpt": AH_ARCH_GPT, "llama": AH_ARCH_LLAMA, "bert": AH_ARCH_BERT}
 PARAM_INDEX = {"ln1_g": 0, "ln1_b": 1, "wqkv": 2, "bqkv": 3, "wo": 4, "bo": 5,
                "ln2_g": 6, "ln2_b": 7, "w1": 8, "b1": 9, "w2": 10, "b2": 11}
 # names the layer's tensors go by elsewhere (LLaMA: fused gate|up and down)
@@ -32,7 +33,7 @@ class StageConfig(C.Structure):
     @classmethod
     def make(cls, arch="gpt", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=1024, tp=1, tp_rank=0, seq=128, mb=1,
              n_mb=1, max_in_flight=1, recompute=0, norm_eps=0.0, rope_base=0.0):
-        return cls(C.sizeof(cls), AH_ARCH_LLAMA if arch == "llama" else AH_ARCH_GPT, n_layers, hidden, n_heads, head_dim,
+        return cls(C.sizeof(cls), _ARCH[arch], n_layers, hidden, n_heads, head_dim,
                    ffn, tp, tp_rank, seq, mb, n_mb, max_in_flight, recompute, norm_eps, rope_base)
 
 
@@ -94,8 +95,8 @@ def _load():
     L.ah_gemm_nn.argtypes = [vp, vp, vp, vp, i, i, i, vp]
     L.ah_gemm_nt.argtypes = [vp, vp, vp, i, i, i, vp]
     L.ah_gemm_tn.argtypes = [vp, vp, vp, i, i, i, i, vp]
-    L.ah_attention_fwd.argtypes = [vp, vp, vp, i, i, i, i, vp]
-    L.ah_attention_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, vp]
+    L.ah_attention_fwd.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+    L.ah_attention_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
     return L
 
 
@@ -216,12 +217,12 @@ def gemm_tn(A, B, Cout, beta, stream=None):
     _check(lib.ah_gemm_tn(_ptr(A), _ptr(B), _ptr(Cout), M, B.shape[1], K, int(beta), _stream(stream)))
 
 
-def attention_fwd(qkv, o, lse, B, S, nh, d, stream=None):
-    _check(lib.ah_attention_fwd(_ptr(qkv), _ptr(o), _ptr(lse), B, S, nh, d, _stream(stream)))
+def attention_fwd(qkv, o, lse, B, S, nh, d, causal=True, stream=None):
+    _check(lib.ah_attention_fwd(_ptr(qkv), _ptr(o), _ptr(lse), B, S, nh, d, int(bool(causal)), _stream(stream)))
 
 
-def attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, stream=None):
-    _check(lib.ah_attention_bwd(_ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(delta), B, S, nh, d, _stream(stream)))
+def attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, causal=True, stream=None):
+    _check(lib.ah_attention_bwd(_ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(delta), B, S, nh, d, int(bool(causal)), _stream(stream)))
 
 
 # ---- cost model (include/ah_cost.h): host arrays in, numbers out

@@ -1,4 +1,4 @@
-// Fused causal self-attention for gfx950, forward and backward, on the packed
+// Fused self-attention (causal or bidirectional) for gfx950, forward and backward, on the packed
 // projection output qkv[T, 3*nh*d] ([Q | K | V], head-major).  No S x S matrix
 // ever reaches HBM: scores are produced tile by tile with MFMA 32x32x16, the
 // softmax runs in fp32 registers (base-2 exponent), and the backward pass
@@ -17,7 +17,8 @@
 //
 // Backward is two deterministic kernels (no atomics): one block per 128 keys
 // accumulates dK and dV over the query tiles at or after it, one block per 128
-// queries accumulates dQ over the key tiles at or before it.
+// queries accumulates dQ over the key tiles at or before it (causal; without the
+// mask both walk every tile of the sequence).
 #include "common.h"
 #include "kernels.h"
 
@@ -84,11 +85,11 @@ struct FwdState {
   float m, l;
 };
 
-template <int D>
+template <int D, bool CAUSAL>
 __device__ __forceinline__ void fwd_tile(const char* __restrict__ cK, const char* __restrict__ cV, FwdState<D>& st, int k0,
                                          int q, int qw0, float sc2, int lane) {
   const int hf = lane >> 5;
-  if (k0 > qw0 + 31) return;  // every key of this tile is after every query of the wave
+  if (CAUSAL && k0 > qw0 + 31) return;  // every key of this tile is after every query of the wave
   f32x16 s[2];
 #pragma unroll
   for (int t = 0; t < 2; t++) {
@@ -98,7 +99,7 @@ __device__ __forceinline__ void fwd_tile(const char* __restrict__ cK, const char
     for (int ks = 0; ks < D / 16; ks++)
       s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rowmajor<D>(cK, t * 32 + (lane & 31), ks, hf), st.qf[ks], s[t], 0, 0, 0);
   }
-  const bool diag = k0 + 63 > qw0;
+  const bool diag = CAUSAL && k0 + 63 > qw0;
   float mx = -INFINITY;
 #pragma unroll
   for (int t = 0; t < 2; t++)
@@ -140,16 +141,16 @@ __device__ __forceinline__ void fwd_tile(const char* __restrict__ cK, const char
     }
 }
 
-template <int D>
+template <int D, bool CAUSAL>
 __device__ __forceinline__ void fwd_step(const bf16* gK, const bf16* gV, const uint32_t* off, char* __restrict__ nK,
                                          char* __restrict__ nV, const char* __restrict__ cK, const char* __restrict__ cV,
                                          FwdState<D>& st, int k0, int q, int qw0, float sc2, int wave, int lane) {
   issue_tile<D>(gK, off, nK, wave);
   issue_tile<D>(gV, off, nV, wave);
-  fwd_tile<D>(cK, cV, st, k0, q, qw0, sc2, lane);
+  fwd_tile<D, CAUSAL>(cK, cV, st, k0, q, qw0, sc2, lane);
 }
 
-template <int D>
+template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
                                                        int S, int nh, float sc2) {
   constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, LPS = 2 * (D / 32);  // ring slot = K tile then V tile
@@ -180,10 +181,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict
 #pragma unroll
   for (int i = 0; i < D / 32; i++) off[i] = tile_src_offset<D>(wave + 4 * i, lane, ld);
 
-  // key tiles of 64 up to and including the diagonal.  Tile t lives in ring slot t % NSLOT; the tile
-  // loaded during step j is min(j + NSLOT - 1, last): past the end the last tile is fetched again into a dead
-  // slot, which keeps the number of loads in flight uniform for the counted wait.
-  const int ntile = 2 * qb + 2, last = ntile - 1;
+  // key tiles of 64 up to and including the diagonal (all of them without the mask).  Tile t lives in ring
+  // slot t % NSLOT; the tile loaded during step j is min(j + NSLOT - 1, last): past the end the last tile is
+  // fetched again into a dead slot, which keeps the number of loads in flight uniform for the counted wait.
+  const int ntile = CAUSAL ? 2 * qb + 2 : S / 64, last = ntile - 1;
   const size_t step = (size_t)64 * ld;
 #pragma unroll
   for (int t = 0; t < NSLOT - 1; t++) {
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict
     const size_t o = (size_t)min(j + NSLOT - 1, last) * step;
     char* fill = ring + ((j + NSLOT - 1) & (NSLOT - 1)) * STAGE;
     const char* cur = ring + (j & (NSLOT - 1)) * STAGE;
-    fwd_step<D>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
+    fwd_step<D, CAUSAL>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
     __builtin_amdgcn_s_barrier();
   }
@@ -249,12 +250,12 @@ struct DqState {
   float lse2, delta;
 };
 
-template <int D>
+template <int D, bool CAUSAL>
 __device__ __forceinline__ void dq_tile(const char* __restrict__ cK, const char* __restrict__ cV, DqState<D>& st, int k0, int q,
                                         int qw0, float sc2, int lane) {
   const int hf = lane >> 5;
-  if (k0 > qw0 + 31) return;
-  const bool diag = k0 + 63 > qw0;
+  if (CAUSAL && k0 > qw0 + 31) return;
+  const bool diag = CAUSAL && k0 + 63 > qw0;
 #pragma unroll
   for (int t = 0; t < 2; t++) {
     f32x16 s, dp;
@@ -284,16 +285,16 @@ __device__ __forceinline__ void dq_tile(const char* __restrict__ cK, const char*
   }
 }
 
-template <int D>
+template <int D, bool CAUSAL>
 __device__ __forceinline__ void dq_step(const bf16* gK, const bf16* gV, const uint32_t* off, char* __restrict__ nK,
                                         char* __restrict__ nV, const char* __restrict__ cK, const char* __restrict__ cV,
                                         DqState<D>& st, int k0, int q, int qw0, float sc2, int wave, int lane) {
   issue_tile<D>(gK, off, nK, wave);
   issue_tile<D>(gV, off, nV, wave);
-  dq_tile<D>(cK, cV, st, k0, q, qw0, sc2, lane);
+  dq_tile<D, CAUSAL>(cK, cV, st, k0, q, qw0, sc2, lane);
 }
 
-template <int D>
+template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
                                                       const float* __restrict__ lse, const float* __restrict__ delta,
                                                       bf16* __restrict__ dqkv, int S, int nh, float sc2, float scale) {
@@ -329,10 +330,10 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict_
 #pragma unroll
   for (int i = 0; i < D / 32; i++) off[i] = tile_src_offset<D>(wave + 4 * i, lane, ld);
 
-  // key tiles of 64 up to and including the diagonal.  Tile t lives in ring slot t % NSLOT; the tile
-  // loaded during step j is min(j + NSLOT - 1, last): past the end the last tile is fetched again into a dead
-  // slot, which keeps the number of loads in flight uniform for the counted wait.
-  const int ntile = 2 * qb + 2, last = ntile - 1;
+  // key tiles of 64 up to and including the diagonal (all of them without the mask).  Tile t lives in ring
+  // slot t % NSLOT; the tile loaded during step j is min(j + NSLOT - 1, last): past the end the last tile is
+  // fetched again into a dead slot, which keeps the number of loads in flight uniform for the counted wait.
+  const int ntile = CAUSAL ? 2 * qb + 2 : S / 64, last = ntile - 1;
   const size_t step = (size_t)64 * ld;
 #pragma unroll
   for (int t = 0; t < NSLOT - 1; t++) {
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict_
     const size_t o = (size_t)min(j + NSLOT - 1, last) * step;
     char* fill = ring + ((j + NSLOT - 1) & (NSLOT - 1)) * STAGE;
     const char* cur = ring + (j & (NSLOT - 1)) * STAGE;
-    dq_step<D>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
+    dq_step<D, CAUSAL>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
     __builtin_amdgcn_s_barrier();
   }
@@ -371,13 +372,13 @@ struct DkvState {
   f32x16 dk[D / 32], dv[D / 32];
 };
 
-template <int D>
+template <int D, bool CAUSAL>
 __device__ __forceinline__ void dkv_tile(const char* __restrict__ cQ, const char* __restrict__ cO, DkvState<D>& st,
                                          const float* __restrict__ lse_tile, const float* __restrict__ delta_tile, int q0, int key,
                                          int kw0, float sc2, int lane) {
   const int hf = lane >> 5;
-  if (q0 + 63 < kw0) return;  // every query of this tile is before every key of the wave
-  const bool diag = q0 < kw0 + 31;
+  if (CAUSAL && q0 + 63 < kw0) return;  // every query of this tile is before every key of the wave
+  const bool diag = CAUSAL && q0 < kw0 + 31;
 #pragma unroll
   for (int t = 0; t < 2; t++) {
     f32x16 s, dp;
@@ -430,16 +431,16 @@ __device__ __forceinline__ void dkv_issue(const bf16* gQ, const bf16* gO, const 
   __builtin_amdgcn_global_load_lds(src, AH_LDS(slot + 2 * TILEB + wave * 256), 4, 0, 0);
 }
 
-template <int D>
+template <int D, bool CAUSAL>
 __device__ __forceinline__ void dkv_step(const bf16* gQ, const bf16* gO, const float* gL, const float* gD, const uint32_t* offq,
                                          const uint32_t* offo, char* __restrict__ fill, const char* __restrict__ cur, DkvState<D>& st,
                                          int q0, int key, int kw0, float sc2, int wave, int lane) {
   constexpr int TILEB = 64 * 2 * D;
   dkv_issue<D>(gQ, gO, gL, gD, offq, offo, fill, wave, lane);
-  dkv_tile<D>(cur, cur + TILEB, st, (const float*)(cur + 2 * TILEB), (const float*)(cur + 2 * TILEB + 256), q0, key, kw0, sc2, lane);
+  dkv_tile<D, CAUSAL>(cur, cur + TILEB, st, (const float*)(cur + 2 * TILEB), (const float*)(cur + 2 * TILEB + 256), q0, key, kw0, sc2, lane);
 }
 
-template <int D>
+template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
                                                        const float* __restrict__ lse, const float* __restrict__ delta,
                                                        bf16* __restrict__ dqkv, int S, int nh, float sc2, float scale) {
@@ -478,9 +479,9 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(const bf16* __restrict__ 
     offo[i] = tile_src_offset<D>(wave + 4 * i, lane, ldo);
   }
 
-  // query tiles of 64 from the diagonal on.  Tile t lives in ring slot t % 4; past the end the last
-  // tile is fetched again into a dead slot (uniform number of loads in flight for the counted wait).
-  const int j0 = 2 * kb, ntile = S / 64 - j0, last = ntile - 1;
+  // query tiles of 64 from the diagonal on (from 0 without the mask).  Tile t lives in ring slot t % 4; past the
+  // end the last tile is fetched again into a dead slot (uniform number of loads in flight for the counted wait).
+  const int j0 = CAUSAL ? 2 * kb : 0, ntile = S / 64 - j0, last = ntile - 1;
   qp += (size_t)j0 * 64 * ld;
   dop += (size_t)j0 * 64 * ldo;
   lse_row += j0 * 64;
@@ -495,7 +496,7 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(const bf16* __restrict__ 
   __builtin_amdgcn_s_barrier();
   for (int j = 0; j < ntile; j++) {
     const int tf = min(j + 3, last);
-    dkv_step<D>(qp + tf * stepq, dop + tf * stepo, lse_row + tf * 64, delta_row + tf * 64, offq, offo, ring + ((j + 3) & 3) * STAGE,
+    dkv_step<D, CAUSAL>(qp + tf * stepq, dop + tf * stepo, lse_row + tf * 64, delta_row + tf * 64, offq, offo, ring + ((j + 3) & 3) * STAGE,
                 ring + (j & 3) * STAGE, st, (j0 + j) * 64, key, kw0, sc2, wave, lane);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
     __builtin_amdgcn_s_barrier();
@@ -523,19 +524,37 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(const bf16* __restrict__ 
 
 static bool attn_shape_ok(int B, int S, int nh, int d) { return B > 0 && nh > 0 && S > 0 && S % 128 == 0 && (d == 64 || d == 128); }
 
-hipError_t launch_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, hipStream_t s) {
+template <int D, bool CAUSAL>
+static void launch_fwd_t(dim3 grid, hipStream_t s, const void* qkv, void* o, float* lse, int S, int nh, float sc2) {
+  hipLaunchKernelGGL((attn_fwd_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, S, nh, sc2);
+}
+
+hipError_t launch_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, bool causal, hipStream_t s) {
   if (!attn_shape_ok(B, S, nh, d)) return hipErrorInvalidValue;
   const float sc2 = LOG2E / sqrtf((float)d);
   const dim3 grid(B * nh * (S / 128));
-  if (d == 128)
-    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, S, nh, sc2);
-  else
-    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, S, nh, sc2);
+  if (d == 128) {
+    if (causal) launch_fwd_t<128, true>(grid, s, qkv, o, lse, S, nh, sc2);
+    else launch_fwd_t<128, false>(grid, s, qkv, o, lse, S, nh, sc2);
+  } else {
+    if (causal) launch_fwd_t<64, true>(grid, s, qkv, o, lse, S, nh, sc2);
+    else launch_fwd_t<64, false>(grid, s, qkv, o, lse, S, nh, sc2);
+  }
   return hipGetLastError();
 }
 
+template <int D, bool CAUSAL>
+static void launch_bwd_t(dim3 grid, dim3 dgrid, hipStream_t s, const void* qkv, const void* o, const float* lse, const void* d_o,
+                         void* dqkv, float* delta, int T, int S, int nh, float sc2, float scale) {
+  hipLaunchKernelGGL(attn_delta_kernel<D>, dgrid, dim3(256), 0, s, (const bf16*)o, (const bf16*)d_o, delta, T, S, nh);
+  hipLaunchKernelGGL((attn_dkv_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv,
+                     S, nh, sc2, scale);
+  hipLaunchKernelGGL((attn_dq_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv,
+                     S, nh, sc2, scale);
+}
+
 hipError_t launch_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
-                                int B, int S, int nh, int d, hipStream_t s) {
+                                int B, int S, int nh, int d, bool causal, hipStream_t s) {
   if (!attn_shape_ok(B, S, nh, d)) return hipErrorInvalidValue;
   const float scale = 1.f / sqrtf((float)d), sc2 = LOG2E * scale;
   const int T = B * S;
@@ -543,17 +562,11 @@ hipError_t launch_attention_bwd(const void* qkv, const void* o, const float* lse
   const long nthreads = (long)T * nh * (d / 8);
   const dim3 dgrid((unsigned)((nthreads + 255) / 256));
   if (d == 128) {
-    hipLaunchKernelGGL(attn_delta_kernel<128>, dgrid, dim3(256), 0, s, (const bf16*)o, (const bf16*)d_o, delta, T, S, nh);
-    hipLaunchKernelGGL(attn_dkv_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv, S,
-                       nh, sc2, scale);
-    hipLaunchKernelGGL(attn_dq_kernel<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv, S,
-                       nh, sc2, scale);
+    if (causal) launch_bwd_t<128, true>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
+    else launch_bwd_t<128, false>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
   } else {
-    hipLaunchKernelGGL(attn_delta_kernel<64>, dgrid, dim3(256), 0, s, (const bf16*)o, (const bf16*)d_o, delta, T, S, nh);
-    hipLaunchKernelGGL(attn_dkv_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv, S,
-                       nh, sc2, scale);
-    hipLaunchKernelGGL(attn_dq_kernel<64>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv, S,
-                       nh, sc2, scale);
+    if (causal) launch_bwd_t<64, true>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
+    else launch_bwd_t<64, false>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
   }
   return hipGetLastError();
 }

@@ -33,9 +33,10 @@ hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, h
 bool gemm_shape_ok(int M, int N, int K);
 
 // ---- attention (d = 64 or 128, S multiple of 128) ----
-hipError_t launch_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, hipStream_t s);
+// causal: query i attends to keys 0..i of its sequence; otherwise to all S keys
+hipError_t launch_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, bool causal, hipStream_t s);
 hipError_t launch_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                                float* delta, int B, int S, int nh, int d, hipStream_t s);
+                                float* delta, int B, int S, int nh, int d, bool causal, hipStream_t s);
 
 // ---- row-wise / element-wise kernels (bf16 I/O, fp32 math) ----
 // a = norm(x) * gamma (+ beta); stats[2*T] = (mean, rstd) per row (RMS: mean slot unused = 0)

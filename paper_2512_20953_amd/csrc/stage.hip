@@ -35,7 +35,7 @@ struct ah_stage {
   ah_stage_config_t cfg;
   ah_stage_buffers_t bufs;
   int T, h, nh, d, hl, F, L;
-  bool llama, recompute;
+  bool llama, causal, recompute;
   float eps, rope_base;
   ParamEntry ptab[AH_P_COUNT];
   uint64_t layer_elems;
@@ -58,7 +58,7 @@ namespace {
 int validate(const ah_stage_config_t* c) {
   if (!c) return set_error(AH_EINVAL, "config is NULL");
   if (c->struct_size != sizeof(ah_stage_config_t)) return set_error(AH_EINVAL, "config.struct_size %u != %zu", c->struct_size, sizeof(ah_stage_config_t));
-  if (c->arch != AH_ARCH_GPT && c->arch != AH_ARCH_LLAMA) return set_error(AH_EINVAL, "unknown arch %d", c->arch);
+  if (c->arch != AH_ARCH_GPT && c->arch != AH_ARCH_LLAMA && c->arch != AH_ARCH_BERT) return set_error(AH_EINVAL, "unknown arch %d", c->arch);
   if (c->n_layers < 1 || c->n_layers > 1024) return set_error(AH_EINVAL, "n_layers %d out of range [1, 1024]", c->n_layers);
   if (c->tp_degree < 1 || c->tp_rank < 0 || c->tp_rank >= c->tp_degree) return set_error(AH_EINVAL, "bad tp_degree/tp_rank %d/%d", c->tp_degree, c->tp_rank);
   if (c->n_heads < 1 || c->ffn_hidden < 1 || c->hidden < 1 || c->seq_len < 1 || c->microbatch_size < 1)
@@ -88,6 +88,7 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
   s->F = c->ffn_hidden / c->tp_degree;
   s->T = c->microbatch_size * c->seq_len;
   s->llama = c->arch == AH_ARCH_LLAMA;
+  s->causal = c->arch != AH_ARCH_BERT;
   s->recompute = c->recompute != 0;
   s->eps = c->norm_eps > 0 ? c->norm_eps : (s->llama ? 1e-6f : 1e-5f);
   s->rope_base = c->rope_base > 0 ? c->rope_base : 10000.f;
@@ -277,7 +278,7 @@ hipError_t layer_forward(ah_stage* s, int layer, const ActPtrs& a, void* y, hipS
   TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_in, p.ln1_g, p.ln1_b, a.a, (float*)a.stats1, T, h, s->eps, st));
   TRY(gemm(s, SITE_QKV_FWD, GEMM_NN, EPI_BF16, a.a, h, p.wqkv, 3 * hl, a.qkv, 3 * hl, T, 3 * hl, h, p.bqkv, nullptr, 0, nullptr, 0, st));
   if (s->llama) TIMED(SITE_ROPE, launch_rope(a.qkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, 1.f, st));
-  TIMED(SITE_ATTN_FWD, launch_attention_fwd(a.qkv, a.o, (float*)a.lse, B, S, s->nh, s->d, st));
+  TIMED(SITE_ATTN_FWD, launch_attention_fwd(a.qkv, a.o, (float*)a.lse, B, S, s->nh, s->d, s->causal, st));
   TRY(gemm(s, SITE_WO_FWD, GEMM_NN, EPI_RESID, a.o, hl, p.wo, h, a.x_mid, h, T, h, hl, p.bo, a.x_in, h, nullptr, 0, st));
   TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_mid, p.ln2_g, p.ln2_b, a.c, (float*)a.stats2, T, h, s->eps, st));
   if (!s->llama) {
@@ -322,7 +323,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   TRY(gemm(s, SITE_WO_WGRAD, GEMM_TN, EPI_F32_ACC, a.o, hl, dmid, h, p.g_wo, h, hl, h, T, nullptr, nullptr, 0, nullptr, beta, st));
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
   // attention
-  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dbig, delta, B, S, s->nh, s->d, st));
+  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dbig, delta, B, S, s->nh, s->d, s->causal, st));
   if (s->llama) TIMED(SITE_ROPE, launch_rope(dbig, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
   if (!s->llama) {
     TIMED(SITE_COLSUM, launch_colsum_partial(dbig, T, 3 * hl, 3 * hl, part, st));
@@ -564,12 +565,12 @@ extern "C" int ah_stage_trace_end(ah_stage_t* st, ah_trace_entry_t* out, int cap
     launches[st->ev_site[i / 2]]++;
   }
   st->ev_used = 0;
-  // algorithmic work per launch: 2*M*N*K flops for the GEMMs, causal-half flops for attention
+  // algorithmic work per launch: 2*M*N*K flops for the GEMMs, causal-half flops for masked attention (all S*S pairs without the mask)
   // (forward 4*d*S*(S+1)/2 per head, backward 2.5x that as executed by the recompute-in-tile scheme
   // counts as 2x model flops), bytes moved once for the bandwidth-bound kernels.
   const double T = st->T, h = st->h, hl = st->hl, F = st->F, Fu = st->llama ? 2.0 * st->F : st->F;
   const double S = st->cfg.seq_len, B = st->cfg.microbatch_size;
-  const double attn = 4.0 * st->d * (S * (S + 1) / 2) * st->nh * B;
+  const double attn = 4.0 * st->d * (st->causal ? S * (S + 1) / 2 : S * S) * st->nh * B;
   double flops[SITE_COUNT] = {0}, bytes[SITE_COUNT] = {0};
   flops[SITE_QKV_FWD] = flops[SITE_QKV_WGRAD] = flops[SITE_QKV_DGRAD] = 2 * T * h * 3 * hl;
   flops[SITE_WO_FWD] = flops[SITE_WO_WGRAD] = flops[SITE_WO_DGRAD] = 2 * T * hl * h;
@@ -596,17 +597,17 @@ extern "C" int ah_stage_trace_end(ah_stage_t* st, ah_trace_entry_t* out, int cap
   return AH_OK;
 }
 
-extern "C" int ah_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, void* stream) {
+extern "C" int ah_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, int causal, void* stream) {
   discard_stale_hip_error();
   if (!qkv || !o || !lse) return set_error(AH_EINVAL, "ah_attention_fwd: NULL pointer");
   if (B < 1 || nh < 1 || S < 1 || S % 128 || (d != 64 && d != 128)) return set_error(AH_EUNSUPPORTED, "ah_attention_fwd: need S %% 128 == 0 and d in {64, 128}");
-  return hip_status(launch_attention_fwd(qkv, o, lse, B, S, nh, d, (hipStream_t)stream), "ah_attention_fwd");
+  return hip_status(launch_attention_fwd(qkv, o, lse, B, S, nh, d, causal != 0, (hipStream_t)stream), "ah_attention_fwd");
 }
 
 extern "C" int ah_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta, int B,
-                                int S, int nh, int d, void* stream) {
+                                int S, int nh, int d, int causal, void* stream) {
   discard_stale_hip_error();
   if (!qkv || !o || !lse || !d_o || !dqkv || !delta) return set_error(AH_EINVAL, "ah_attention_bwd: NULL pointer");
   if (B < 1 || nh < 1 || S < 1 || S % 128 || (d != 64 && d != 128)) return set_error(AH_EUNSUPPORTED, "ah_attention_bwd: need S %% 128 == 0 and d in {64, 128}");
-  return hip_status(launch_attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, (hipStream_t)stream), "ah_attention_bwd");
+  return hip_status(launch_attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, causal != 0, (hipStream_t)stream), "ah_attention_bwd");
 }

@@ -37,7 +37,7 @@ def test_all_workloads_are_supported_and_sized(name):
     s = query_sizes(_cfg(name))
     nh, hl, F = SI.local_dims(w)
     h = w["hidden"]
-    if w["arch"] == "gpt":
+    if w["arch"] != "llama":
         per_layer = 6 * h + h * 3 * hl + 3 * hl + hl * h + h * F + F + F * h
     else:
         per_layer = 2 * h + h * 3 * hl + hl * h + 3 * h * F
@@ -102,4 +102,4 @@ def test_gemm_entry_points_refuse_bad_shapes_without_touching_the_device():
     assert lib.ah_gemm_nn(1, 1, None, 1, 100, 128, 128, None) == 5
     assert lib.ah_gemm_nt(None, 1, 1, 128, 128, 128, None) == 1
     assert lib.ah_gemm_tn(1, 1, 1, 128, 128, 128, 2, None) == 1
-    assert lib.ah_attention_fwd(1, 1, 1, 1, 100, 1, 128, None) == 5
+    assert lib.ah_attention_fwd(1, 1, 1, 1, 100, 1, 128, 1, None) == 5

@@ -68,8 +68,9 @@ def test_gemm_at_benchmark_shapes_sampled_entries(layout, M, N, K):
         assert U.rel_l2(U.to_np(C)[np.ix_(rows, cols)], ref0) <= tol
 
 
-@pytest.mark.parametrize("B,S,nh,d", [(2, 2048, 16, 128), (1, 4096, 32, 128)])
-def test_attention_at_benchmark_shapes_sampled_heads(B, S, nh, d):
+@pytest.mark.parametrize("B,S,nh,d,causal", [(2, 2048, 16, 128, True), (1, 4096, 32, 128, True), (8, 512, 16, 64, False),
+                                              (1, 2048, 4, 128, False)])
+def test_attention_at_benchmark_shapes_sampled_heads(B, S, nh, d, causal):
     rng = np.random.default_rng(8)
     T, hl = B * S, nh * d
     qkv = _bf16_normal(rng, (T, 3 * hl), 1.0)
@@ -79,28 +80,29 @@ def test_attention_at_benchmark_shapes_sampled_heads(B, S, nh, d):
     lse = torch.empty(B * nh * S, dtype=torch.float32, device="cuda")
     dqkv = torch.empty(T, 3 * hl, dtype=torch.bfloat16, device="cuda")
     delta = torch.empty(B * nh * S, dtype=torch.float32, device="cuda")
-    P.attention_fwd(qkv_d, o, lse, B, S, nh, d)
-    P.attention_bwd(qkv_d, o, lse, do_d, dqkv, delta, B, S, nh, d)
+    P.attention_fwd(qkv_d, o, lse, B, S, nh, d, causal)
+    P.attention_bwd(qkv_d, o, lse, do_d, dqkv, delta, B, S, nh, d, causal)
     torch.cuda.synchronize()
     o_np, dqkv_np, lse_np = U.to_np(o), U.to_np(dqkv), lse.cpu().numpy().reshape(B, nh, S)
     for (b, j) in [(0, 0), (B - 1, nh - 1), (0, nh // 2)]:
         rows = slice(b * S, (b + 1) * S)
         q, k, v = (qkv[rows, blk * hl + j * d: blk * hl + (j + 1) * d].astype(np.float64)[None, None] for blk in range(3))
         do = d_o[rows, j * d:(j + 1) * d].astype(np.float64)[None, None]
-        ro = R.attention_fwd(q, k, v)[0, 0]
-        rdq, rdk, rdv = (t[0, 0] for t in R.attention_bwd(q, k, v, do))
+        ro = R.attention_fwd(q, k, v, causal)[0, 0]
+        rdq, rdk, rdv = (t[0, 0] for t in R.attention_bwd(q, k, v, do, causal))
         assert U.rel_l2(o_np[rows, j * d:(j + 1) * d], ro) <= 2e-2
         for blk, ref in enumerate((rdq, rdk, rdv)):
             assert U.rel_l2(dqkv_np[rows, blk * hl + j * d: blk * hl + (j + 1) * d], ref) <= 3e-2, (b, j, blk)
-        # log-sum-exp of the scaled causal scores, from its definition
+        # log-sum-exp of the scaled (causal: masked) scores, from its definition
         s = (q[0, 0] @ k[0, 0].T) / np.sqrt(d)
-        s[np.triu_indices(S, 1)] = -np.inf
+        if causal:
+            s[np.triu_indices(S, 1)] = -np.inf
         m = s.max(-1)
         ref_lse = m + np.log(np.exp(s - m[:, None]).sum(-1))
         assert np.abs(lse_np[b, j] - ref_lse).max() <= 2e-2
 
 
-@pytest.mark.parametrize("name", ["gpt1p3b", "gpt7b_tp2", "gpt13b", "llama7b"])
+@pytest.mark.parametrize("name", ["gpt1p3b", "gpt7b_tp2", "gpt13b", "llama7b", "bert_large"])
 def test_one_full_size_layer_of_each_workload(name):
     w = dict(SI.WORKLOADS[name], n_layers=1, n_mb=1)
     gcfg, ocfg = U.make_cfgs(w)

@@ -48,6 +48,9 @@ REDUCED = {
     "gpt_d128_tp2": dict(arch="gpt", n_layers=2, hidden=384, n_heads=4, head_dim=128, ffn=1536, seq=384, mb=2, n_mb=3, tp=2, recompute=0),
     "llama_small": dict(arch="llama", n_layers=2, hidden=512, n_heads=4, head_dim=128, ffn=768, seq=256, mb=1, n_mb=2, tp=1, recompute=0),
     "llama_d64": dict(arch="llama", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=384, seq=128, mb=2, n_mb=2, tp=1, recompute=0),
+    # bidirectional attention: 3 query / key blocks with head_dim 128 on a TP shard; 2 blocks with head_dim 64
+    "bert_d128_tp2": dict(arch="bert", n_layers=2, hidden=384, n_heads=4, head_dim=128, ffn=1536, seq=384, mb=2, n_mb=2, tp=2, recompute=0),
+    "bert_tiny": SI.WORKLOADS["bert_tiny"],
 }
 
 
@@ -166,3 +169,38 @@ def test_layer_times_add_up_as_the_profiler_assumes():
     assert abs(r["rel_err"]) < 0.10
     assert r["activation_bytes_estimated"] == r["activation_bytes_measured"]
     assert abs(sum(prof[3]["fwd_ms"]) - prof[3]["stage_fwd_ms"]) <= 0.1 * prof[3]["stage_fwd_ms"]
+
+
+def test_bidirectional_stage_is_permutation_equivariant_and_differs_from_causal():
+    """Mask work of the bidirectional path: with no positional signal inside the stage, reversing the
+    tokens of every sequence reverses the outputs (to rounding: the tiles are summed in another order),
+    a late token reaches the first output, and the causal stage on the same inputs gives another result."""
+    w = SI.WORKLOADS["bert_tiny"]
+    gcfg, _ = U.make_cfgs(w)
+    params, xs, dys = _inputs(w, n_mb=1)
+    st = P.Stage(gcfg)
+    U.load_params(st, params)
+    B, S, h = w["mb"], w["seq"], w["hidden"]
+    x = xs[0].reshape(B, S, h)
+
+    def fwd(stage, xin):
+        xd = U.to_dev(xin.reshape(B * S, h))
+        y = torch.empty_like(xd)
+        stage.forward(0, xd, y)
+        dx = torch.empty_like(xd)
+        stage.backward(0, U.to_dev(dys[0]), dx)   # frees the slot
+        torch.cuda.synchronize()
+        return U.to_np(y).reshape(B, S, h)
+
+    y = fwd(st, x)
+    yr = fwd(st, x[:, ::-1])
+    assert U.rel_l2(yr, y[:, ::-1]) <= 1e-2
+    x2 = x.copy()
+    x2[:, -1] = x[:, -1][:, ::-1]
+    assert np.abs(fwd(st, x2)[:, 0] - y[:, 0]).max() > 0
+    cst = P.Stage(U.make_cfgs(dict(w, arch="gpt"))[0])
+    U.load_params(cst, params)
+    yc = fwd(cst, x)
+    assert np.array_equal(yc[:, 0], fwd(cst, x2)[:, 0])      # causal: position 0 never sees the last token
+    # position 0 attends to itself alone under the mask and to all S keys without it (rounding noise is ~3e-3)
+    assert U.rel_l2(yc[:, 0], y[:, 0]) > 1e-2
