@@ -29,6 +29,9 @@ constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr int NSLOT = 2;  // ring slots of the forward and dQ kernels (two blocks share a CU)
 
+// nothing is scheduled across this point
+#define AH_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 // LDS tile [64 rows][D] bf16.  16-byte piece p of row r is stored at piece
 // swz(r, p): conflict-free both for 16-byte reads down a column of pieces and
 // for the transposing reads of 4 rows x 64 bytes.
@@ -77,6 +80,16 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int s2) {
 
 __device__ __forceinline__ float fexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Query block of a thread block under the causal mask (block qb walks 2*qb + 2 key tiles).  A launch that
+// fits on the chip at once (two blocks per CU, 256 CUs) is placed statically, blocks i and i + grid/2 on
+// the same CU, so the second half of the grid runs the light blocks in ascending order and every CU gets
+// the same total; a larger launch is dispatched as CUs free up and simply goes heaviest first.
+__device__ __forceinline__ int causal_query_block(int r, int nq) {
+  if (gridDim.x > 512) return nq - 1 - r;
+  const int half = (nq + 1) / 2;
+  return r < half ? nq - 1 - r : r - half;
+}
+
 // =========================================================================== forward
 template <int D>
 struct FwdState {
@@ -85,69 +98,100 @@ struct FwdState {
   float m, l;
 };
 
-template <int D, bool CAUSAL>
+// The running maximum is only raised when a new score exceeds it by more than this many powers of two:
+// probabilities are then at most 2^8 instead of 1, which fp32 sums and the bf16 operand of the second
+// product hold with unchanged relative accuracy, and the rescaling of the output accumulator -- the
+// largest block of vector arithmetic in the loop -- runs on the first tile only in practice.
+constexpr float RESCALE_SLACK = 8.f;
+
+// One key tile of 64 for the wave's 32 queries.  LDS reads are issued a phase ahead of their use (see
+// dkv_tile); the mask costs vector work only on tiles that straddle the diagonal (diag is wave-uniform).
+template <int D>
 __device__ __forceinline__ void fwd_tile(const char* __restrict__ cK, const char* __restrict__ cV, FwdState<D>& st, int k0,
-                                         int q, int qw0, float sc2, int lane) {
+                                         int q, bool diag, float sc2, int lane) {
+  constexpr int NK = D / 16, ND = D / 32;
   const int hf = lane >> 5;
-  if (CAUSAL && k0 > qw0 + 31) return;  // every key of this tile is after every query of the wave
-  f32x16 s[2];
+  bf16x8 fk0[NK], fk1[NK];
 #pragma unroll
-  for (int t = 0; t < 2; t++) {
+  for (int ks = 0; ks < NK; ks++) fk0[ks] = frag_rowmajor<D>(cK, lane & 31, ks, hf);
+  AH_SCHED_FENCE();
+  f32x16 s0, s1;
 #pragma unroll
-    for (int r = 0; r < 16; r++) s[t][r] = 0.f;
+  for (int r = 0; r < 16; r++) { s0[r] = 0.f; s1[r] = 0.f; }
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ks++)
-      s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rowmajor<D>(cK, t * 32 + (lane & 31), ks, hf), st.qf[ks], s[t], 0, 0, 0);
-  }
-  const bool diag = CAUSAL && k0 + 63 > qw0;
-  float mx = -INFINITY;
+  for (int ks = 0; ks < NK; ks++) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk0[ks], st.qf[ks], s0, 0, 0, 0);
 #pragma unroll
-  for (int t = 0; t < 2; t++)
+  for (int ks = 0; ks < NK; ks++) fk1[ks] = frag_rowmajor<D>(cK, 32 + (lane & 31), ks, hf);
+  AH_SCHED_FENCE();
+  bf16x8 v0[2][ND], v1[2][ND];
+#pragma unroll
+  for (int ks = 0; ks < NK; ks++) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk1[ks], st.qf[ks], s1, 0, 0, 0);
+#pragma unroll
+  for (int s2 = 0; s2 < 2; s2++)
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++) v0[s2][dt] = frag_transposed<D>(cV, 16 * s2 + 4 * hf, dt, lane);
+  AH_SCHED_FENCE();
+  if (diag) {
+    // element r of half t is key k0 + t*32 + 8*(r/4) + 4*hf + r%4: masked iff that exceeds q
+    const int lim = q - k0 - 4 * hf;
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-      const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-      float v = s[t][r] * sc2;
-      if (diag && key > q) v = -INFINITY;
-      s[t][r] = v;
-      mx = fmaxf(mx, v);
+      if (8 * (r >> 2) + (r & 3) > lim) s0[r] = -INFINITY;
+      if (32 + 8 * (r >> 2) + (r & 3) > lim) s1[r] = -INFINITY;
     }
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-  const float m_new = fmaxf(st.m, mx);
-  const float alpha = fexp2(st.m - m_new);
-  st.m = m_new;
+  }
+  float mx = fmaxf(s0[0], s1[0]);
+#pragma unroll
+  for (int r = 1; r < 16; r++) mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc2;
+  if (__any(mx > st.m + RESCALE_SLACK)) {  // wave-uniform branch
+    const float m_new = fmaxf(st.m, mx);
+    const float alpha = fexp2(st.m - m_new);
+    st.m = m_new;
+    st.l *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) st.oacc[dt][r] *= alpha;
+  }
+  const float nm = -st.m;
   float ls = 0.f;
 #pragma unroll
-  for (int t = 0; t < 2; t++)
+  for (int r = 0; r < 16; r++) {
+    s0[r] = fexp2(__builtin_fmaf(s0[r], sc2, nm));
+    s1[r] = fexp2(__builtin_fmaf(s1[r], sc2, nm));
+    ls += s0[r] + s1[r];
+  }
+  st.l += ls;
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const float p = fexp2(s[t][r] - m_new);
-      s[t][r] = p;
-      ls += p;
-    }
-  st.l = st.l * alpha + ls;
+  for (int s2 = 0; s2 < 2; s2++)
 #pragma unroll
-  for (int dt = 0; dt < D / 32; dt++)
+    for (int dt = 0; dt < ND; dt++) v1[s2][dt] = frag_transposed<D>(cV, 32 + 16 * s2 + 4 * hf, dt, lane);
+  AH_SCHED_FENCE();
 #pragma unroll
-    for (int r = 0; r < 16; r++) st.oacc[dt][r] *= alpha;
+  for (int s2 = 0; s2 < 2; s2++) {
+    const bf16x8 pf = pack8(s0, s2);
 #pragma unroll
-  for (int t = 0; t < 2; t++)
+    for (int dt = 0; dt < ND; dt++) st.oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0[s2][dt], pf, st.oacc[dt], 0, 0, 0);
+  }
 #pragma unroll
-    for (int s2 = 0; s2 < 2; s2++) {
-      const bf16x8 pf = pack8(s[t], s2);
+  for (int s2 = 0; s2 < 2; s2++) {
+    const bf16x8 pf = pack8(s1, s2);
 #pragma unroll
-      for (int dt = 0; dt < D / 32; dt++)
-        st.oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed<D>(cV, t * 32 + 16 * s2 + 4 * hf, dt, lane), pf,
-                                                             st.oacc[dt], 0, 0, 0);
-    }
+    for (int dt = 0; dt < ND; dt++) st.oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1[s2][dt], pf, st.oacc[dt], 0, 0, 0);
+  }
+  AH_SCHED_FENCE();
 }
 
-template <int D, bool CAUSAL>
+// MAY_SKIP: the tile may lie wholly after the wave's queries (only the last tile of a block, under the mask)
+template <int D, bool CAUSAL, bool MAY_SKIP>
 __device__ __forceinline__ void fwd_step(const bf16* gK, const bf16* gV, const uint32_t* off, char* __restrict__ nK,
                                          char* __restrict__ nV, const char* __restrict__ cK, const char* __restrict__ cV,
                                          FwdState<D>& st, int k0, int q, int qw0, float sc2, int wave, int lane) {
   issue_tile<D>(gK, off, nK, wave);
   issue_tile<D>(gV, off, nV, wave);
-  fwd_tile<D, CAUSAL>(cK, cV, st, k0, q, qw0, sc2, lane);
+  if (CAUSAL && MAY_SKIP && k0 > qw0 + 31) return;
+  fwd_tile<D>(cK, cV, st, k0, q, CAUSAL && k0 + 63 > qw0, sc2, lane);
 }
 
 template <int D, bool CAUSAL>
@@ -159,7 +203,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: LDS bases stay scalar
   const int nbh = gridDim.x / (S / 128);
   const int bh = blockIdx.x % nbh;
-  const int qb = S / 128 - 1 - blockIdx.x / nbh;  // heaviest query blocks first
+  const int qb = CAUSAL ? causal_query_block(blockIdx.x / nbh, S / 128) : blockIdx.x / nbh;
   const int b = bh / nh, head = bh % nh;
   const int ld = 3 * nh * D;
   const bf16* qp = qkv + (size_t)b * S * ld + head * D;
@@ -194,13 +238,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
   __builtin_amdgcn_s_barrier();
-  for (int j = 0; j < ntile; j++) {
+  // Only the last tile can lie wholly after a wave's queries (waves 0 and 1 under the mask): it is peeled so
+  // that the loop body has a single path.
+  for (int j = 0; j < last; j++) {
     const size_t o = (size_t)min(j + NSLOT - 1, last) * step;
     char* fill = ring + ((j + NSLOT - 1) & (NSLOT - 1)) * STAGE;
     const char* cur = ring + (j & (NSLOT - 1)) * STAGE;
-    fwd_step<D, CAUSAL>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
+    fwd_step<D, CAUSAL, false>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
     __builtin_amdgcn_s_barrier();
+  }
+  {
+    const size_t o = (size_t)last * step;
+    char* fill = ring + ((last + NSLOT - 1) & (NSLOT - 1)) * STAGE;
+    const char* cur = ring + (last & (NSLOT - 1)) * STAGE;
+    fwd_step<D, CAUSAL, true>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, last * 64, q, qw0, sc2, wave, lane);
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant tail loads
 
@@ -250,48 +302,89 @@ struct DqState {
   float lse2, delta;
 };
 
-template <int D, bool CAUSAL>
+// One key tile of 64 for the wave's 32 queries.  With head_dim 64 the LDS reads run a phase ahead of their
+// use as in dkv_tile; with head_dim 128 the 256 registers of a wave (two blocks share a CU) leave no room
+// for fragments in flight, so they are fetched where they are used and the other block covers the wait.
+template <int D>
 __device__ __forceinline__ void dq_tile(const char* __restrict__ cK, const char* __restrict__ cV, DqState<D>& st, int k0, int q,
-                                        int qw0, float sc2, int lane) {
+                                        bool diag, float sc2, int lane) {
+  constexpr int NK = D / 16, ND = D / 32;
+  constexpr bool AHEAD = D == 64;
   const int hf = lane >> 5;
-  if (CAUSAL && k0 > qw0 + 31) return;
-  const bool diag = CAUSAL && k0 + 63 > qw0;
+  const int lim = q - k0 - 4 * hf;  // element r of half t is masked iff t*32 + 8*(r/4) + r%4 > lim
+  bf16x8 fk[NK], fv[NK];
+  if (AHEAD) {
+#pragma unroll
+    for (int ks = 0; ks < NK; ks++) {
+      fk[ks] = frag_rowmajor<D>(cK, lane & 31, ks, hf);
+      fv[ks] = frag_rowmajor<D>(cV, lane & 31, ks, hf);
+    }
+  }
 #pragma unroll
   for (int t = 0; t < 2; t++) {
+    if (AHEAD) AH_SCHED_FENCE();
     f32x16 s, dp;
 #pragma unroll
     for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
-    const int row = t * 32 + (lane & 31);
+    bf16x8 kt[2][ND];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) {
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rowmajor<D>(cK, row, ks, hf), st.qf[ks], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rowmajor<D>(cV, row, ks, hf), st.dof[ks], dp, 0, 0, 0);
+    for (int ks = 0; ks < NK; ks++) {
+      if (!AHEAD) {
+        fk[ks] = frag_rowmajor<D>(cK, t * 32 + (lane & 31), ks, hf);
+        fv[ks] = frag_rowmajor<D>(cV, t * 32 + (lane & 31), ks, hf);
+      }
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[ks], st.qf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[ks], st.dof[ks], dp, 0, 0, 0);
     }
+    if (AHEAD) {
+#pragma unroll
+      for (int s2 = 0; s2 < 2; s2++)
+#pragma unroll
+        for (int dt = 0; dt < ND; dt++) kt[s2][dt] = frag_transposed<D>(cK, t * 32 + 16 * s2 + 4 * hf, dt, lane);
+      AH_SCHED_FENCE();
+    }
+    const float nl = -st.lse2;
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-      const int key = k0 + t * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-      float p = fexp2(s[r] * sc2 - st.lse2);
-      if (diag && key > q) p = 0.f;
-      s[r] = p * (dp[r] - st.delta);  // dS^T
+      s[r] = fexp2(__builtin_fmaf(s[r], sc2, nl));
+      dp[r] -= st.delta;
     }
+    if (diag) {  // wave-uniform
+#pragma unroll
+      for (int r = 0; r < 16; r++)
+        if (t * 32 + 8 * (r >> 2) + (r & 3) > lim) s[r] = 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; r++) s[r] *= dp[r];  // dS^T
+    if (AHEAD && t == 0) {
+#pragma unroll
+      for (int ks = 0; ks < NK; ks++) {
+        fk[ks] = frag_rowmajor<D>(cK, 32 + (lane & 31), ks, hf);
+        fv[ks] = frag_rowmajor<D>(cV, 32 + (lane & 31), ks, hf);
+      }
+    }
+    if (AHEAD) AH_SCHED_FENCE();
 #pragma unroll
     for (int s2 = 0; s2 < 2; s2++) {
       const bf16x8 dsf = pack8(s, s2);
 #pragma unroll
-      for (int dt = 0; dt < D / 32; dt++)
-        st.acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed<D>(cK, t * 32 + 16 * s2 + 4 * hf, dt, lane), dsf,
-                                                            st.acc[dt], 0, 0, 0);
+      for (int dt = 0; dt < ND; dt++) {
+        if (!AHEAD) kt[s2][dt] = frag_transposed<D>(cK, t * 32 + 16 * s2 + 4 * hf, dt, lane);
+        st.acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[s2][dt], dsf, st.acc[dt], 0, 0, 0);
+      }
     }
   }
+  if (AHEAD) AH_SCHED_FENCE();
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool MAY_SKIP>
 __device__ __forceinline__ void dq_step(const bf16* gK, const bf16* gV, const uint32_t* off, char* __restrict__ nK,
                                         char* __restrict__ nV, const char* __restrict__ cK, const char* __restrict__ cV,
                                         DqState<D>& st, int k0, int q, int qw0, float sc2, int wave, int lane) {
   issue_tile<D>(gK, off, nK, wave);
   issue_tile<D>(gV, off, nV, wave);
-  dq_tile<D, CAUSAL>(cK, cV, st, k0, q, qw0, sc2, lane);
+  if (CAUSAL && MAY_SKIP && k0 > qw0 + 31) return;
+  dq_tile<D>(cK, cV, st, k0, q, CAUSAL && k0 + 63 > qw0, sc2, lane);
 }
 
 template <int D, bool CAUSAL>
@@ -304,7 +397,7 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict_
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: LDS bases stay scalar
   const int nbh = gridDim.x / (S / 128);
   const int bh = blockIdx.x % nbh;
-  const int qb = S / 128 - 1 - blockIdx.x / nbh;
+  const int qb = CAUSAL ? causal_query_block(blockIdx.x / nbh, S / 128) : blockIdx.x / nbh;
   const int b = bh / nh, head = bh % nh;
   const int ld = 3 * nh * D;
   const bf16* qp = qkv + (size_t)b * S * ld + head * D;
@@ -343,13 +436,19 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict_
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
   __builtin_amdgcn_s_barrier();
-  for (int j = 0; j < ntile; j++) {
+  for (int j = 0; j < last; j++) {
     const size_t o = (size_t)min(j + NSLOT - 1, last) * step;
     char* fill = ring + ((j + NSLOT - 1) & (NSLOT - 1)) * STAGE;
     const char* cur = ring + (j & (NSLOT - 1)) * STAGE;
-    dq_step<D, CAUSAL>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
+    dq_step<D, CAUSAL, false>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, j * 64, q, qw0, sc2, wave, lane);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NSLOT - 2) * LPS));
     __builtin_amdgcn_s_barrier();
+  }
+  {  // the last tile, peeled as in the forward kernel
+    const size_t o = (size_t)last * step;
+    char* fill = ring + ((last + NSLOT - 1) & (NSLOT - 1)) * STAGE;
+    const char* cur = ring + (last & (NSLOT - 1)) * STAGE;
+    dq_step<D, CAUSAL, true>(kp + o, vp + o, off, fill, fill + TILEB, cur, cur + TILEB, st, last * 64, q, qw0, sc2, wave, lane);
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant tail loads
 
@@ -372,50 +471,89 @@ struct DkvState {
   f32x16 dk[D / 32], dv[D / 32];
 };
 
-template <int D, bool CAUSAL>
+// One query tile of 64 for the wave's 32 keys.  Every fragment comes out of LDS, which all four waves
+// share and which is the busiest unit of this kernel, so the reads are issued one phase ahead of their
+// use (scheduling fences keep the compiler from sinking them back to the point of use): the transposed
+// fragments of the second pair of products are requested while the first pair runs and while the
+// probabilities are rebuilt, the row-major fragments of the next half while the second pair runs.
+template <int D>
 __device__ __forceinline__ void dkv_tile(const char* __restrict__ cQ, const char* __restrict__ cO, DkvState<D>& st,
                                          const float* __restrict__ lse_tile, const float* __restrict__ delta_tile, int q0, int key,
-                                         int kw0, float sc2, int lane) {
+                                         bool diag, float sc2, int lane) {
+  constexpr int NK = D / 16, ND = D / 32;
   const int hf = lane >> 5;
-  if (CAUSAL && q0 + 63 < kw0) return;  // every query of this tile is before every key of the wave
-  const bool diag = CAUSAL && q0 < kw0 + 31;
+  const int lim = key - q0 - 4 * hf;  // query offset ql (without the 4*hf term) is masked iff ql < lim
+  bf16x8 fq[NK], fo[NK];
+#pragma unroll
+  for (int ks = 0; ks < NK; ks++) {
+    fq[ks] = frag_rowmajor<D>(cQ, lane & 31, ks, hf);
+    fo[ks] = frag_rowmajor<D>(cO, lane & 31, ks, hf);
+  }
 #pragma unroll
   for (int t = 0; t < 2; t++) {
+    AH_SCHED_FENCE();
     f32x16 s, dp;
 #pragma unroll
     for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
-    const int row = t * 32 + (lane & 31);
+    bf16x8 tq0[ND], to0[ND], tq1[ND], to1[ND];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) {
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rowmajor<D>(cQ, row, ks, hf), st.kf[ks], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rowmajor<D>(cO, row, ks, hf), st.vf[ks], dp, 0, 0, 0);
+    for (int ks = 0; ks < NK; ks++) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[ks], st.kf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[ks], st.vf[ks], dp, 0, 0, 0);
     }
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++) {
+      to0[dt] = frag_transposed<D>(cO, t * 32 + 4 * hf, dt, lane);
+      tq0[dt] = frag_transposed<D>(cQ, t * 32 + 4 * hf, dt, lane);
+    }
+    AH_SCHED_FENCE();
     // lane holds queries q0 + t*32 + 8g + 4hf + i of its key
 #pragma unroll
     for (int g = 0; g < 4; g++) {
-      const int ql = t * 32 + 8 * g + 4 * hf, qq = q0 + ql;
+      const int ql = t * 32 + 8 * g + 4 * hf;
       const f32x4 l4 = *(const f32x4*)(lse_tile + ql);
       const f32x4 d4 = *(const f32x4*)(delta_tile + ql);
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         const int r = 4 * g + i;
-        float p = fexp2(s[r] * sc2 - l4[i] * LOG2E);
-        if (diag && key > qq + i) p = 0.f;
-        s[r] = p;
-        dp[r] = p * (dp[r] - d4[i]);
+        s[r] = fexp2(__builtin_fmaf(s[r], sc2, -l4[i] * LOG2E));
+        dp[r] -= d4[i];
       }
     }
+    if (diag) {  // wave-uniform: only tiles that straddle the diagonal pay for the mask
 #pragma unroll
-    for (int s2 = 0; s2 < 2; s2++) {
-      const bf16x8 pf = pack8(s, s2), dsf = pack8(dp, s2);
-      const int rbase = t * 32 + 16 * s2 + 4 * hf;
+      for (int r = 0; r < 16; r++)
+        if (t * 32 + 8 * (r >> 2) + (r & 3) < lim) s[r] = 0.f;
+    }
 #pragma unroll
-      for (int dt = 0; dt < D / 32; dt++) {
-        st.dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed<D>(cO, rbase, dt, lane), pf, st.dv[dt], 0, 0, 0);
-        st.dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed<D>(cQ, rbase, dt, lane), dsf, st.dk[dt], 0, 0, 0);
+    for (int r = 0; r < 16; r++) dp[r] *= s[r];
+    AH_SCHED_FENCE();
+    const bf16x8 pf0 = pack8(s, 0), dsf0 = pack8(dp, 0), pf1 = pack8(s, 1), dsf1 = pack8(dp, 1);
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++) {
+      to1[dt] = frag_transposed<D>(cO, t * 32 + 16 + 4 * hf, dt, lane);
+      tq1[dt] = frag_transposed<D>(cQ, t * 32 + 16 + 4 * hf, dt, lane);
+    }
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++) {
+      st.dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to0[dt], pf0, st.dv[dt], 0, 0, 0);
+      st.dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq0[dt], dsf0, st.dk[dt], 0, 0, 0);
+    }
+    AH_SCHED_FENCE();
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++) {
+      st.dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to1[dt], pf1, st.dv[dt], 0, 0, 0);
+      st.dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq1[dt], dsf1, st.dk[dt], 0, 0, 0);
+    }
+    if (t == 0) {
+#pragma unroll
+      for (int ks = 0; ks < NK; ks++) {
+        fq[ks] = frag_rowmajor<D>(cQ, 32 + (lane & 31), ks, hf);
+        fo[ks] = frag_rowmajor<D>(cO, 32 + (lane & 31), ks, hf);
       }
     }
   }
+  AH_SCHED_FENCE();
 }
 
 // ring slot of the dK/dV kernel: Q tile, dO tile, then 64 log-sum-exps, 64 deltas and 512 spare bytes
@@ -431,13 +569,16 @@ __device__ __forceinline__ void dkv_issue(const bf16* gQ, const bf16* gO, const 
   __builtin_amdgcn_global_load_lds(src, AH_LDS(slot + 2 * TILEB + wave * 256), 4, 0, 0);
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool MAY_SKIP>
 __device__ __forceinline__ void dkv_step(const bf16* gQ, const bf16* gO, const float* gL, const float* gD, const uint32_t* offq,
                                          const uint32_t* offo, char* __restrict__ fill, const char* __restrict__ cur, DkvState<D>& st,
                                          int q0, int key, int kw0, float sc2, int wave, int lane) {
   constexpr int TILEB = 64 * 2 * D;
   dkv_issue<D>(gQ, gO, gL, gD, offq, offo, fill, wave, lane);
-  dkv_tile<D, CAUSAL>(cur, cur + TILEB, st, (const float*)(cur + 2 * TILEB), (const float*)(cur + 2 * TILEB + 256), q0, key, kw0, sc2, lane);
+  const float* lse_tile = (const float*)(cur + 2 * TILEB);
+  if (CAUSAL && MAY_SKIP && q0 + 63 < kw0) return;  // every query of this tile is before every key of the wave
+  // diag: the tile straddles the diagonal of this wave's keys (wave-uniform)
+  dkv_tile<D>(cur, cur + TILEB, st, lse_tile, lse_tile + 64, q0, key, CAUSAL && q0 < kw0 + 31, sc2, lane);
 }
 
 template <int D, bool CAUSAL>
@@ -494,10 +635,19 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(const bf16* __restrict__ 
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
   __builtin_amdgcn_s_barrier();
-  for (int j = 0; j < ntile; j++) {
+  // Only the block's first tile can lie wholly before a wave's keys (waves 2 and 3 under the mask); it is
+  // peeled so that the loop body has a single path and the accumulators stay where the MFMAs want them.
+  {
+    const int tf = min(3, last);
+    dkv_step<D, CAUSAL, true>(qp + tf * stepq, dop + tf * stepo, lse_row + tf * 64, delta_row + tf * 64, offq, offo, ring + 3 * STAGE, ring,
+                              st, j0 * 64, key, kw0, sc2, wave, lane);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+    __builtin_amdgcn_s_barrier();
+  }
+  for (int j = 1; j < ntile; j++) {
     const int tf = min(j + 3, last);
-    dkv_step<D, CAUSAL>(qp + tf * stepq, dop + tf * stepo, lse_row + tf * 64, delta_row + tf * 64, offq, offo, ring + ((j + 3) & 3) * STAGE,
-                ring + (j & 3) * STAGE, st, (j0 + j) * 64, key, kw0, sc2, wave, lane);
+    dkv_step<D, CAUSAL, false>(qp + tf * stepq, dop + tf * stepo, lse_row + tf * 64, delta_row + tf * 64, offq, offo,
+                               ring + ((j + 3) & 3) * STAGE, ring + (j & 3) * STAGE, st, (j0 + j) * 64, key, kw0, sc2, wave, lane);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
     __builtin_amdgcn_s_barrier();
   }
