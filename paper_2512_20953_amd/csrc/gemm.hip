@@ -322,13 +322,17 @@ namespace {
 
 // Tile choice: the 256-CU chip runs one block per CU, so a launch costs
 // ceil(tiles / 256) rounds of one tile's time.  Relative tile costs (per output
-// element) are measured constants: smaller tiles re-read more from LDS and L2.
-struct TileCfg { int bm, bn, wgm, wgn; float cost; };
-const TileCfg kTiles[] = {{256, 256, 2, 2, 1.00f}, {256, 128, 2, 2, 1.12f}, {128, 256, 2, 2, 1.12f}, {128, 128, 2, 2, 1.35f}};
+// element) are measured constants: smaller tiles re-read more from LDS and L2
+// (4096 x 6144 x 4096, NN: 384 tiles of 256 x 256 in two rounds take 211 us, 768
+// tiles of 256 x 128 in three rounds 219 us, i.e. 1.35 per element; the weight
+// gradient, whose epilogue moves twice the bytes per tile, loses less: 1.25).
+struct TileCfg { int bm, bn, wgm, wgn; float cost, cost_tn; };
+const TileCfg kTiles[] = {{256, 256, 2, 2, 1.00f, 1.00f}, {256, 128, 2, 2, 1.35f, 1.25f}, {128, 256, 2, 2, 1.35f, 1.25f},
+                          {128, 128, 2, 2, 1.60f, 1.50f}};
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int kAutoTiles = 4;  // the automatic choice looks at the first kAutoTiles entries
 
-int pick_tile(int M, int N) {
+int pick_tile(int M, int N, bool tn) {
   static int forced = -2;
   if (forced == -2) {
     const char* e = getenv("AH_GEMM_TILE");  // tuning aid: index into kTiles
@@ -341,7 +345,7 @@ int pick_tile(int M, int N) {
     if (M % kTiles[i].bm || N % kTiles[i].bn) continue;
     long tiles = (long)(M / kTiles[i].bm) * (N / kTiles[i].bn);
     long rounds = (tiles + 255) / 256;
-    float t = rounds * kTiles[i].cost * kTiles[i].bm * kTiles[i].bn;
+    float t = rounds * (tn ? kTiles[i].cost_tn : kTiles[i].cost) * kTiles[i].bm * kTiles[i].bn;
     if (best < 0 || t < best_t) { best = i; best_t = t; }
   }
   return best;
@@ -372,7 +376,7 @@ hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in
   if (grp < 0) { grp = getenv("AH_GEMM_GROUP") ? atoi(getenv("AH_GEMM_GROUP")) : 8; remap = getenv("AH_GEMM_NOREMAP") ? 0 : 1; }
   a.group = grp; a.xcd_remap = remap;
   if (!gemm_shape_ok(a.M, a.N, a.K)) return hipErrorInvalidValue;
-  const int t = pick_tile(a.M, a.N);
+  const int t = pick_tile(a.M, a.N, layout == GEMM_TN);
   if (t < 0) return hipErrorInvalidValue;
   if (layout == GEMM_NN) {
     if (epi == EPI_BF16) return run_tile<false, true, EPI_BF16>(t, a, s);

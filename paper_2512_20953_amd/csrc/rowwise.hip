@@ -5,6 +5,7 @@
 // written once, 16 bytes per lane, statistics and sums in fp32.
 #include "common.h"
 #include "kernels.h"
+#include <cstdlib>
 
 namespace ah {
 
@@ -85,110 +86,134 @@ __global__ __launch_bounds__(NT) void norm_fwd_kernel(const bf16* __restrict__ x
 }
 
 // ---------------------------------------------------------------- norm backward
-// Block b handles rows [b*rpb, (b+1)*rpb); a thread keeps its columns for all of them, so the
-// three column sums accumulate in registers and leave the block once.  Rows go through in
-// batches of RB (4 for hidden <= 4096): their loads are all in flight together and one block reduction serves the batch.
+// Block b handles rows b, b + nblk, b + 2*nblk, ... (so that the blocks, which advance together, read one
+// contiguous stretch of memory at a time and spread over all HBM channels); a thread keeps its columns for
+// all of them, so the three column sums accumulate in registers and leave the block once.  512 threads (two waves per
+// SIMD), rows in batches of RB; the loads of the next batch are issued before the current one is
+// reduced, so that memory latency, the block reduction and the arithmetic overlap.
+constexpr int NTB = 512;  // threads per block of the norm backward; MAXC here = ceil(hidden / 4096)
+
 template <bool RMS, int MAXC>
-__global__ __launch_bounds__(NT) void norm_bwd_kernel(const bf16* __restrict__ da, const bf16* __restrict__ x,
-                                                      const float* __restrict__ stats, const bf16* __restrict__ gamma,
-                                                      const bf16* __restrict__ dres, bf16* __restrict__ dx,
-                                                      float* __restrict__ part, int T, int h, int rpb) {
-  constexpr int RB = MAXC <= 2 ? 4 : (MAXC <= 4 ? 2 : 1);  // rows per batch, bounded by the register file
-  __shared__ float red[4][2 * RB];
+__global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ da, const bf16* __restrict__ x,
+                                                       const float* __restrict__ stats, const bf16* __restrict__ gamma,
+                                                       const bf16* __restrict__ dres, bf16* __restrict__ dx,
+                                                       float* __restrict__ part, int T, int h, int rpb) {
+  constexpr int RB = MAXC <= 1 ? 4 : (MAXC <= 2 ? 2 : 1);  // rows per batch, bounded by the register file
+  constexpr int NWV = NTB / 64;
+  constexpr bool PIPE = MAXC <= 2;  // wider rows (hidden > 8192) leave no registers for a second batch, and spill a few
+  __shared__ float red[2][NWV][2 * RB];                     // double-buffered: one block barrier per batch
   const int nchunk = h >> 3, nblk = gridDim.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float inv_h = 1.f / h;
   float gam[MAXC][8], s_g[MAXC][8], s_b[MAXC][8], s_r[MAXC][8];
 #pragma unroll
   for (int i = 0; i < MAXC; i++) {
-    const int c = threadIdx.x + i * NT;
+    const int c = threadIdx.x + i * NTB;
     if (c < nchunk) {
       bf16x8 g = *(const bf16x8*)(gamma + c * 8);
 #pragma unroll
       for (int j = 0; j < 8; j++) { gam[i][j] = bf2f(g[j]); s_g[i][j] = 0.f; s_b[i][j] = 0.f; s_r[i][j] = 0.f; }
     }
   }
-  const int r0 = blockIdx.x * rpb, r1 = min(T, r0 + rpb);
-  for (int rb = r0; rb < r1; rb += RB) {
-    float xh[RB][MAXC][8], w[RB][MAXC][8], rstd[RB], sums[2 * RB];
-    bf16x8 tx[RB][MAXC], td[RB][MAXC];
-    // all loads of the batch first, so that they are in flight together
+  // the block's rows are j * nblk + blockIdx.x for j in [r0, r1)
+  const int r0 = 0, r1 = (T - (int)blockIdx.x + nblk - 1) / nblk;
+  bf16x8 tx[RB][MAXC], td[RB][MAXC], tr[RB][MAXC];   // current batch
+  bf16x8 nx[PIPE ? RB : 1][PIPE ? MAXC : 1], nd[PIPE ? RB : 1][PIPE ? MAXC : 1], nr[PIPE ? RB : 1][PIPE ? MAXC : 1];  // next batch
+  float mean[RB], rstd[RB], nmean[PIPE ? RB : 1], nrstd[PIPE ? RB : 1];
+  // a short last batch repeats its last row; the copies are computed but neither summed nor stored
+  auto fetch = [&](int rb, auto& fx, auto& fd, auto& fr, auto& fm, auto& fs) {
 #pragma unroll
     for (int k = 0; k < RB; k++) {
-      const int row = min(rb + k, r1 - 1);   // a short last batch repeats its last row; the copy is not used
+      const int row = min(rb + k, r1 - 1) * nblk + blockIdx.x;
 #pragma unroll
       for (int i = 0; i < MAXC; i++) {
-        const int c = threadIdx.x + i * NT;
+        const int c = threadIdx.x + i * NTB;
         if (c < nchunk) {
-          tx[k][i] = *(const bf16x8*)(x + (size_t)row * h + c * 8);
-          td[k][i] = *(const bf16x8*)(da + (size_t)row * h + c * 8);
+          fx[k][i] = *(const bf16x8*)(x + (size_t)row * h + c * 8);
+          fd[k][i] = *(const bf16x8*)(da + (size_t)row * h + c * 8);
+          fr[k][i] = *(const bf16x8*)(dres + (size_t)row * h + c * 8);
         }
       }
+      fm[k] = RMS ? 0.f : stats[2 * row];
+      fs[k] = stats[2 * row + 1];
     }
+  };
+  if (PIPE && r0 < r1) fetch(r0, tx, td, tr, mean, rstd);
+  int buf = 0;
+  for (int rb = r0; rb < r1; rb += RB, buf ^= 1) {
+    if constexpr (PIPE) {
+      if (rb + RB < r1) fetch(rb + RB, nx, nd, nr, nmean, nrstd);
+    } else {
+      fetch(rb, tx, td, tr, mean, rstd);
+    }
+    float sums[2 * RB];
 #pragma unroll
     for (int k = 0; k < RB; k++) {
-      const int row = min(rb + k, r1 - 1);
-      const float mean = stats[2 * row];
-      rstd[k] = stats[2 * row + 1];
+      const bool live = rb + k < r1;
+      const float nm = -mean[k] * rstd[k];
       float sw = 0.f, swx = 0.f;
 #pragma unroll
       for (int i = 0; i < MAXC; i++) {
-        const int c = threadIdx.x + i * NT;
-        if (c < nchunk) {
+        if (threadIdx.x + i * NTB < nchunk) {
 #pragma unroll
           for (int j = 0; j < 8; j++) {
             const float d = bf2f(td[k][i][j]);
-            xh[k][i][j] = (bf2f(tx[k][i][j]) - mean) * rstd[k];
-            w[k][i][j] = d * gam[i][j];
-            sw += w[k][i][j];
-            swx += w[k][i][j] * xh[k][i][j];
-            if (rb + k < r1) { s_g[i][j] += d * xh[k][i][j]; s_b[i][j] += d; }
+            const float xh = __builtin_fmaf(bf2f(tx[k][i][j]), rstd[k], nm);
+            const float w = d * gam[i][j];
+            sw += w;
+            swx = __builtin_fmaf(w, xh, swx);
+            if (live) { s_g[i][j] = __builtin_fmaf(d, xh, s_g[i][j]); s_b[i][j] += d; }
           }
         }
       }
       sums[2 * k] = wave_sum(sw);
       sums[2 * k + 1] = wave_sum(swx);
     }
-    bf16x8 tr[RB][MAXC];
-#pragma unroll
-    for (int k = 0; k < RB; k++) {
-      const int row = min(rb + k, r1 - 1);
-#pragma unroll
-      for (int i = 0; i < MAXC; i++) {
-        const int c = threadIdx.x + i * NT;
-        if (c < nchunk) tr[k][i] = *(const bf16x8*)(dres + (size_t)row * h + c * 8);
-      }
-    }
-    __syncthreads();  // red may still be read from the previous batch
     if (lane == 0) {
 #pragma unroll
-      for (int k = 0; k < 2 * RB; k++) red[wave][k] = sums[k];
+      for (int k = 0; k < 2 * RB; k++) red[buf][wave][k] = sums[k];
     }
-    __syncthreads();
+    __syncthreads();  // the other half of red was last read before the previous barrier
 #pragma unroll
     for (int k = 0; k < RB; k++) {
       if (rb + k >= r1) break;
-      const int row = rb + k;
-      const float c1 = RMS ? 0.f : (red[0][2 * k] + red[1][2 * k] + red[2][2 * k] + red[3][2 * k]) / h;
-      const float c2 = (red[0][2 * k + 1] + red[1][2 * k + 1] + red[2][2 * k + 1] + red[3][2 * k + 1]) / h;
+      const int row = (rb + k) * nblk + blockIdx.x;
+      float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+      for (int w8 = 0; w8 < NWV; w8++) { c1 += red[buf][w8][2 * k]; c2 += red[buf][w8][2 * k + 1]; }
+      c1 = RMS ? 0.f : c1 * inv_h;
+      c2 *= inv_h;
+      const float nm = -mean[k] * rstd[k];
 #pragma unroll
       for (int i = 0; i < MAXC; i++) {
-        const int c = threadIdx.x + i * NT;
+        const int c = threadIdx.x + i * NTB;
         if (c < nchunk) {
           bf16x8 o;
 #pragma unroll
           for (int j = 0; j < 8; j++) {
             const float r = bf2f(tr[k][i][j]);
+            const float xh = __builtin_fmaf(bf2f(tx[k][i][j]), rstd[k], nm);
+            const float w = bf2f(td[k][i][j]) * gam[i][j];
             s_r[i][j] += r;
-            o[j] = f2bf(r + rstd[k] * (w[k][i][j] - c1 - xh[k][i][j] * c2));
+            o[j] = f2bf(r + rstd[k] * (w - c1 - xh * c2));
           }
           *(bf16x8*)(dx + (size_t)row * h + c * 8) = o;
         }
       }
     }
+    if constexpr (PIPE) {
+#pragma unroll
+      for (int k = 0; k < RB; k++) {
+        mean[k] = nmean[k];
+        rstd[k] = nrstd[k];
+#pragma unroll
+        for (int i = 0; i < MAXC; i++) { tx[k][i] = nx[k][i]; td[k][i] = nd[k][i]; tr[k][i] = nr[k][i]; }
+      }
+    }
   }
 #pragma unroll
   for (int i = 0; i < MAXC; i++) {
-    const int c = threadIdx.x + i * NT;
+    const int c = threadIdx.x + i * NTB;
     if (c < nchunk) {
       float* p0 = part + ((size_t)0 * nblk + blockIdx.x) * h + c * 8;
       float* p1 = part + ((size_t)1 * nblk + blockIdx.x) * h + c * 8;
@@ -338,12 +363,16 @@ void norm_bwd_go(const void* da, const void* x, const float* stats, const void* 
                  int T, int h, hipStream_t s) {
   const int nblk = norm_bwd_blocks(T);
   const int rpb = (T + nblk - 1) / nblk;
-  hipLaunchKernelGGL((norm_bwd_kernel<RMS, MAXC>), dim3(nblk), dim3(NT), 0, s, (const bf16*)da, (const bf16*)x, stats,
+  hipLaunchKernelGGL((norm_bwd_kernel<RMS, MAXC>), dim3(nblk), dim3(NTB), 0, s, (const bf16*)da, (const bf16*)x, stats,
                      (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, part, T, h, rpb);
 }
 }  // namespace
 
-int norm_bwd_blocks(int T) { return T / 4 < 256 ? (T / 4 > 0 ? T / 4 : 1) : 256; }
+int norm_bwd_blocks(int T) {
+  static int cap = -1;
+  if (cap < 0) cap = getenv("AH_NORM_NBLK") ? atoi(getenv("AH_NORM_NBLK")) : 256;  // tuning aid
+  return T / 4 < cap ? (T / 4 > 0 ? T / 4 : 1) : cap;
+}
 
 #define AH_BY_CHUNKS(FN, RMS, ...)                                   \
   do {                                                               \
@@ -363,11 +392,19 @@ hipError_t launch_norm_fwd(bool rms, const void* x, const void* gamma, const voi
   return hipGetLastError();
 }
 
+#define AH_BWD_BY_CHUNKS(RMS)                                                                        \
+  do {                                                                                               \
+    const int nc = (h + 4095) / 4096;                                                                \
+    if (nc <= 1) norm_bwd_go<RMS, 1>(da, x, stats, gamma, dres, dx, part, T, h, s);                  \
+    else if (nc == 2) norm_bwd_go<RMS, 2>(da, x, stats, gamma, dres, dx, part, T, h, s);             \
+    else norm_bwd_go<RMS, 4>(da, x, stats, gamma, dres, dx, part, T, h, s);                          \
+  } while (0)
+
 hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float* stats, const void* gamma, const void* dres,
                            void* dx, float* part, int T, int h, hipStream_t s) {
   if (h % 8 || h > 16384) return hipErrorInvalidValue;
-  if (rms) AH_BY_CHUNKS(norm_bwd_go, true, da, x, stats, gamma, dres, dx, part, T, h, s);
-  else AH_BY_CHUNKS(norm_bwd_go, false, da, x, stats, gamma, dres, dx, part, T, h, s);
+  if (rms) AH_BWD_BY_CHUNKS(true);
+  else AH_BWD_BY_CHUNKS(false);
   return hipGetLastError();
 }
 
