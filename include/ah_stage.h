@@ -19,6 +19,11 @@
  *  - ah_stage_forward / ah_stage_backward only enqueue work on the HIP stream
  *    passed as `hip_stream` (a hipStream_t cast to void*; NULL = the default
  *    stream) and never synchronise.  ah_stage_profile synchronises.
+ *    ah_stage_backward runs the weight-gradient products and the bias / gain
+ *    reductions on a second stream of its own (created on the first call, at
+ *    the default priority); that stream is ordered after the work it consumes
+ *    and joined back into `hip_stream` before the call returns, so callers see
+ *    ordinary single-stream semantics.
  *  - Matrices are row-major.  Rows of an activation are ordered batch-major:
  *    row = b * seq_len + s.  Linear layers are y = x W + b with W[in, out].
  *  - Activations and parameters are bf16 (bit pattern in uint16_t), gradients
@@ -125,7 +130,7 @@ int ah_stage_query_sizes(const ah_stage_config_t* cfg, ah_stage_sizes_t* out);
 /* Builds a stage over the caller's buffers.  Touches no device memory. */
 int ah_stage_create(const ah_stage_config_t* cfg, const ah_stage_buffers_t* bufs, ah_stage_t** out);
 
-/* Frees host metadata.  The caller must have synchronised the streams it used. */
+/* Frees host metadata and the library's own stream and events.  The caller must have synchronised the streams it used. */
 int ah_stage_destroy(ah_stage_t* st);
 
 /* Where tensor `which` (ah_param_t) of layer `layer` lives: element offset into

@@ -1,6 +1,7 @@
 // Stage object: buffer partitioning, the per-layer kernel sequences of forward
 // and backward, gradient accumulation state, and the profiler.  C ABI in
-// include/ah_stage.h.  Host code only enqueues kernels on the caller's stream.
+// include/ah_stage.h.  Host code only enqueues kernels: on the caller's stream and, for the
+// parts of backward that nothing downstream waits for, on a second stream joined back into it.
 #include "ah_stage.h"
 #include "capi_util.h"
 #include "kernels.h"
@@ -8,6 +9,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -26,7 +28,7 @@ struct ActLayout {
 };
 
 struct Workspace {
-  size_t d0, d1, dmid, dbig, dsm, delta, part, rope, prof_x, prof_dy, prof_y, prof_dx, layer_ws, bytes;
+  size_t d0, d1, dmid, dbig, dsm, delta, part_n2, part_n1, part_b1, part_bqkv, rope, prof_x, prof_dy, prof_y, prof_dx, layer_ws, bytes;
 };
 
 }  // namespace
@@ -48,6 +50,11 @@ struct ah_stage {
   bool rope_ready;
   // optional per-call-site timing (ah_stage_trace_begin / _end)
   bool tracing;
+  // Second stream for the work of backward that nothing downstream waits for (weight gradients, column-sum
+  // reductions); created on first use, joined back into the caller's stream before every return.
+  hipStream_t side;
+  hipEvent_t sync_ev[8];
+  bool side_ready, side_off;
   std::vector<hipEvent_t> ev_pool;           // pairs, in launch order
   std::vector<int> ev_site;                  // site of pair i
   size_t ev_used;
@@ -142,8 +149,11 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
   w.dbig = take(T * std::max<size_t>(Fu, 3 * hl) * 2);
   w.dsm = take(T * std::max<size_t>({(size_t)h, (size_t)hl, (size_t)F}) * 2);
   w.delta = take(T * s->nh * 4);
-  const size_t part_elems = std::max<size_t>((size_t)3 * norm_bwd_blocks(s->T) * h, (size_t)colsum_blocks(s->T) * std::max<size_t>(Fu, 3 * hl));
-  w.part = take(part_elems * 4);
+  // partial column sums: one region per producer, so that the reductions can trail behind on the side stream
+  w.part_n2 = take((size_t)3 * norm_bwd_blocks(s->T) * h * 4);
+  w.part_n1 = take((size_t)3 * norm_bwd_blocks(s->T) * h * 4);
+  w.part_b1 = take(s->llama ? 0 : (size_t)colsum_blocks(s->T) * F * 4);
+  w.part_bqkv = take(s->llama ? 0 : (size_t)colsum_blocks(s->T) * 3 * hl * 4);
   w.rope = take(s->llama ? (size_t)c->seq_len * s->d * 4 : 0);
   w.prof_x = take(T * h * 2);
   w.prof_dy = take(T * h * 2);
@@ -291,50 +301,97 @@ hipError_t layer_forward(ah_stage* s, int layer, const ActPtrs& a, void* y, hipS
   return hipSuccess;
 }
 
-hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, int beta, hipStream_t st) {
+// Lets `to` wait for everything enqueued on `from` so far.  No-op when both are the same stream.
+hipError_t stream_order(hipStream_t from, hipStream_t to, hipEvent_t ev) {
+  if (from == to) return hipSuccess;
+  hipError_t e = hipEventRecord(ev, from);
+  return e != hipSuccess ? e : hipStreamWaitEvent(to, ev, 0);
+}
+
+// One layer backward.  `st` carries the chain every later kernel depends on (input gradients, attention,
+// norms); `sd` (the side stream, or st itself) carries the weight-gradient GEMMs and the column-sum
+// reductions, which only the caller's next use of the gradients waits for.  Each side launch is ordered
+// after its producer on st, st waits for the side stream before a buffer the side stream still reads is
+// rewritten (dbig, by attention backward) and at the end of the layer (workspace and, with recompute, the
+// shared activation working set are reused by the next layer).
+hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, int beta, hipStream_t st, hipStream_t sd) {
   const LayerPtrs p = layer_ptrs(s, layer);
   const int T = s->T, h = s->h, hl = s->hl, F = s->F, B = s->cfg.microbatch_size, S = s->cfg.seq_len;
   char* wsb = (char*)s->bufs.workspace;
   char *dmid = wsb + s->ws.dmid, *dbig = wsb + s->ws.dbig, *dsm = wsb + s->ws.dsm;
-  float* part = (float*)(wsb + s->ws.part);
+  float *part_n2 = (float*)(wsb + s->ws.part_n2), *part_n1 = (float*)(wsb + s->ws.part_n1);
+  float *part_b1 = (float*)(wsb + s->ws.part_b1), *part_bqkv = (float*)(wsb + s->ws.part_bqkv);
   float* delta = (float*)(wsb + s->ws.delta);
   const int nb = norm_bwd_blocks(T), cb = colsum_blocks(T);
   const bool rms = s->llama;
+  hipEvent_t* ev = s->sync_ev;
+#define ON_SIDE(site, expr)              \
+  do {                                   \
+    SiteTimer t_(s, site, sd);           \
+    g_where = #expr;                     \
+    hipError_t e_ = (expr);              \
+    if (e_ != hipSuccess) return e_;     \
+  } while (0)
 
   // second MLP matrix: dW2 += g^T dy ; input gradient of the activation
-  TRY(gemm(s, SITE_FC2_WGRAD, GEMM_TN, EPI_F32_ACC, a.g, F, dy, h, p.g_w2, h, F, h, T, nullptr, nullptr, 0, nullptr, beta, st));
+  TRY(stream_order(st, sd, ev[0]));  // dy is complete
+  TRY(gemm(s, SITE_FC2_WGRAD, GEMM_TN, EPI_F32_ACC, a.g, F, dy, h, p.g_w2, h, F, h, T, nullptr, nullptr, 0, nullptr, beta, sd));
   if (!s->llama) {
     TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, dbig, F, T, F, h, nullptr, a.u, F, nullptr, 0, st));  // du
-    TIMED(SITE_COLSUM, launch_colsum_partial(dbig, T, F, F, part, st));
-    TIMED(SITE_COLSUM, launch_colsum_finish(part, cb, F, p.g_b1, beta, st));
-    TRY(gemm(s, SITE_FC1_WGRAD, GEMM_TN, EPI_F32_ACC, a.c, h, dbig, F, p.g_w1, F, h, F, T, nullptr, nullptr, 0, nullptr, beta, st));
+    TRY(stream_order(st, sd, ev[1]));
+    ON_SIDE(SITE_COLSUM, launch_colsum_partial(dbig, T, F, F, part_b1, sd));
+    ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_b1, cb, F, p.g_b1, beta, sd));
+    TRY(gemm(s, SITE_FC1_WGRAD, GEMM_TN, EPI_F32_ACC, a.c, h, dbig, F, p.g_w1, F, h, F, T, nullptr, nullptr, 0, nullptr, beta, sd));
     TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, dbig, F, p.w1, F, dsm, h, T, h, F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
   } else {
     TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_BF16, dy, h, p.w2, h, dsm, F, T, F, h, nullptr, nullptr, 0, nullptr, 0, st));  // dm
     TIMED(SITE_SWIGLU_BWD, launch_swiglu_bwd(dsm, a.u, dbig, T, F, st));                                                     // d(gate|up)
-    TRY(gemm(s, SITE_FC1_WGRAD, GEMM_TN, EPI_F32_ACC, a.c, h, dbig, 2 * F, p.g_w1, 2 * F, h, 2 * F, T, nullptr, nullptr, 0, nullptr, beta, st));
+    TRY(stream_order(st, sd, ev[1]));
+    TRY(gemm(s, SITE_FC1_WGRAD, GEMM_TN, EPI_F32_ACC, a.c, h, dbig, 2 * F, p.g_w1, 2 * F, h, 2 * F, T, nullptr, nullptr, 0, nullptr, beta, sd));
     TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, dbig, 2 * F, p.w1, 2 * F, dsm, h, T, h, 2 * F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
   }
+  if (sd != st) TRY(hipEventRecord(ev[2], sd));  // the side stream is done with dbig
   // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
-  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part, T, h, st));
-  if (rms) TIMED(SITE_COLSUM, launch_colsum_finish(part, nb, h, p.g_ln2_g, beta, st));
-  else TIMED(SITE_COLSUM, launch_colsum_finish3(part, nb, h, p.g_ln2_g, p.g_ln2_b, p.g_b2, beta, st));
+  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part_n2, T, h, st));
+  TRY(stream_order(st, sd, ev[3]));
+  if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n2, nb, h, p.g_ln2_g, beta, sd));
+  else ON_SIDE(SITE_COLSUM, launch_colsum_finish3(part_n2, nb, h, p.g_ln2_g, p.g_ln2_b, p.g_b2, beta, sd));
   // output projection
-  TRY(gemm(s, SITE_WO_WGRAD, GEMM_TN, EPI_F32_ACC, a.o, hl, dmid, h, p.g_wo, h, hl, h, T, nullptr, nullptr, 0, nullptr, beta, st));
+  TRY(gemm(s, SITE_WO_WGRAD, GEMM_TN, EPI_F32_ACC, a.o, hl, dmid, h, p.g_wo, h, hl, h, T, nullptr, nullptr, 0, nullptr, beta, sd));
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
-  // attention
+  // attention (writes dbig: wait until the first MLP matrix's weight gradient has read it)
+  if (sd != st) TRY(hipStreamWaitEvent(st, ev[2], 0));
   TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dbig, delta, B, S, s->nh, s->d, s->causal, st));
   if (s->llama) TIMED(SITE_ROPE, launch_rope(dbig, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
+  TRY(stream_order(st, sd, ev[4]));
   if (!s->llama) {
-    TIMED(SITE_COLSUM, launch_colsum_partial(dbig, T, 3 * hl, 3 * hl, part, st));
-    TIMED(SITE_COLSUM, launch_colsum_finish(part, cb, 3 * hl, p.g_bqkv, beta, st));
+    ON_SIDE(SITE_COLSUM, launch_colsum_partial(dbig, T, 3 * hl, 3 * hl, part_bqkv, sd));
+    ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_bqkv, cb, 3 * hl, p.g_bqkv, beta, sd));
   }
-  TRY(gemm(s, SITE_QKV_WGRAD, GEMM_TN, EPI_F32_ACC, a.a, h, dbig, 3 * hl, p.g_wqkv, 3 * hl, h, 3 * hl, T, nullptr, nullptr, 0, nullptr, beta, st));
+  TRY(gemm(s, SITE_QKV_WGRAD, GEMM_TN, EPI_F32_ACC, a.a, h, dbig, 3 * hl, p.g_wqkv, 3 * hl, h, 3 * hl, T, nullptr, nullptr, 0, nullptr, beta, sd));
   TRY(gemm(s, SITE_QKV_DGRAD, GEMM_NT, EPI_BF16, dbig, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
   // first norm backward; dx = dx_mid + norm_bwd(da); column sums give d(gain), d(offset), d(bo)
-  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part, T, h, st));
-  if (rms) TIMED(SITE_COLSUM, launch_colsum_finish(part, nb, h, p.g_ln1_g, beta, st));
-  else TIMED(SITE_COLSUM, launch_colsum_finish3(part, nb, h, p.g_ln1_g, p.g_ln1_b, p.g_bo, beta, st));
+  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part_n1, T, h, st));
+  TRY(stream_order(st, sd, ev[5]));
+  if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n1, nb, h, p.g_ln1_g, beta, sd));
+  else ON_SIDE(SITE_COLSUM, launch_colsum_finish3(part_n1, nb, h, p.g_ln1_g, p.g_ln1_b, p.g_bo, beta, sd));
+  TRY(stream_order(sd, st, ev[6]));  // join
+#undef ON_SIDE
+  return hipSuccess;
+}
+
+// The side stream and its events, created on the first backward pass (the device of the caller's buffers is
+// current then).  AH_NO_SIDE_STREAM in the environment keeps everything on the caller's stream (tuning aid).
+hipError_t ensure_side(ah_stage* s) {
+  if (s->side_ready || s->side_off) return hipSuccess;
+  if (getenv("AH_NO_SIDE_STREAM")) { s->side_off = true; return hipSuccess; }
+  hipError_t e = hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking);
+  if (e != hipSuccess) return e;
+  for (auto& v : s->sync_ev) {
+    e = hipEventCreateWithFlags(&v, hipEventDisableTiming);
+    if (e != hipSuccess) return e;
+  }
+  s->side_ready = true;
   return hipSuccess;
 }
 
@@ -365,12 +422,15 @@ hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipSt
   const int beta = s->overwrite_grads ? 0 : 1;
   char* wsb = (char*)s->bufs.workspace;
   const void* cur = dy;
+  TRY(ensure_side(s));
+  // per-site timing wants one kernel at a time: a trace keeps everything on the caller's stream
+  const hipStream_t sd = (s->side_ready && !s->tracing) ? s->side : st;
   if (ev) TRY(hipEventRecord(ev[s->L], st));
   for (int l = s->L - 1; l >= 0; l--) {
     const ActPtrs a = act_ptrs(s, slot, l);
     if (s->recompute) TRY(layer_forward(s, l, a, nullptr, st));
     void* out = (l == 0) ? dx : (void*)(wsb + ((l & 1) ? s->ws.d1 : s->ws.d0));
-    TRY(layer_backward(s, l, a, cur, out, beta, st));
+    TRY(layer_backward(s, l, a, cur, out, beta, st, sd));
     cur = out;
     if (ev) TRY(hipEventRecord(ev[l], st));
   }
@@ -416,6 +476,9 @@ extern "C" int ah_stage_create(const ah_stage_config_t* cfg, const ah_stage_buff
   s->busy.assign(cfg->max_in_flight, 0);
   s->overwrite_grads = true;
   s->rope_ready = false;
+  s->side = nullptr;
+  s->side_ready = false;
+  s->side_off = false;
   s->tracing = false;
   s->ev_used = 0;
   *out = s;
@@ -423,8 +486,14 @@ extern "C" int ah_stage_create(const ah_stage_config_t* cfg, const ah_stage_buff
 }
 
 extern "C" int ah_stage_destroy(ah_stage_t* st) {
-  if (st)
+  if (st) {
     for (hipEvent_t e : st->ev_pool) (void)hipEventDestroy(e);
+    if (st->side_ready) {
+      (void)hipStreamSynchronize(st->side);
+      for (hipEvent_t e : st->sync_ev) (void)hipEventDestroy(e);
+      (void)hipStreamDestroy(st->side);
+    }
+  }
   delete st;
   return AH_OK;
 }
