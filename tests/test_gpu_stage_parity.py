@@ -204,3 +204,28 @@ def test_bidirectional_stage_is_permutation_equivariant_and_differs_from_causal(
     assert np.array_equal(yc[:, 0], fwd(cst, x2)[:, 0])      # causal: position 0 never sees the last token
     # position 0 attends to itself alone under the mask and to all S keys without it (rounding noise is ~3e-3)
     assert U.rel_l2(yc[:, 0], y[:, 0]) > 1e-2
+
+
+@pytest.mark.parametrize("name", ["tiny", "llama_small"])
+def test_second_stream_changes_no_bit(name, monkeypatch):
+    """Backward puts weight gradients and reductions on a stream of its own; with that switched off (everything on
+    the caller's stream) the outputs and every gradient must be bit-identical, also with recompute."""
+    w = SI.WORKLOADS[name] if name in SI.WORKLOADS else REDUCED[name]
+    outs = []
+    for off in (False, True):
+        if off:
+            monkeypatch.setenv("AH_NO_SIDE_STREAM", "1")
+        else:
+            monkeypatch.delenv("AH_NO_SIDE_STREAM", raising=False)
+        for rc in (0, 1):
+            gcfg, _ = U.make_cfgs(w, recompute=rc)
+            params, xs, dys = _inputs(w)
+            st = P.Stage(gcfg)
+            U.load_params(st, params)
+            ys, dxs = U.run_gpu(st, xs, dys)
+            ys2, dxs2 = U.run_gpu(st, xs, dys)          # a second iteration on the same stage (streams already exist)
+            outs.append((ys + dxs + ys2 + dxs2, st.grads.clone()))
+    for arrs, g in outs[1:]:
+        for a, b in zip(arrs, outs[0][0]):
+            assert np.array_equal(a, b)
+        assert torch.equal(g, outs[0][1])
