@@ -1,5 +1,5 @@
 // bf16 GEMM for gfx950: MFMA 32x32x16, fp32 accumulators, tiles staged through
-// LDS by direct global->LDS loads (16 B per lane), double buffered.
+// LDS by direct global->LDS loads (16 B per lane) through a ring of operand tiles.
 //
 // Three operand layouts cover the linear layers of a decoder layer (the GEMM is
 // the core of the stage's time, paper Section II-B):
@@ -19,6 +19,169 @@
 
 namespace ah {
 
+// Two pipelines share the tile mapping and the epilogue.  The forward and input-gradient products (at least
+// one k-contiguous operand) use 64-wide k tiles in a ring of five operand buffers, so that every loader
+// instruction fetches whole 128-byte lines of the k-contiguous operand; the weight gradient (both operands
+// k-strided, rows of a tile are 256 or 512 bytes anyway) keeps 32-wide k stages in a ring of four, whose loads
+// all run 2.5 stages ahead.  Measured in the stage: the first is 2-13 % faster on the former products, the
+// second 1-5 % faster on the latter.
+namespace k64 {
+constexpr int BK = 64;  // k-extent of one operand tile in LDS (128 bytes per row of a k-contiguous operand: whole cache lines)
+constexpr int NB = 5;   // operand tiles in the LDS ring (A and B tiles alternate): 2.5 k-blocks of 64
+
+// ---------------------------------------------------------------------------
+// LDS layouts (all permutations are of 16-byte pieces, the unit of the loader)
+//  k-contiguous tile: [rows][64 k]; row = 128 B = 8 pieces; piece p of row r is
+//    stored at piece p ^ ((r >> 1) & 7): 16 consecutive rows hit 16 distinct
+//    16-byte bank groups for the fragment reads.  A loader instruction fetches
+//    8 rows x 128 B: full cache lines (64-byte row pieces, as a 32-wide k-block
+//    would give, cost the memory pipeline twice the requests and showed up as
+//    ~10 % of MFMA utilisation).
+//  k-strided tile: [64 k][W cols]; row = 2W bytes; the 64-byte granule g of row
+//    k is stored at granule g ^ (k & 3): the 4 rows x 64 B that half a wave
+//    fetches in one transposing read cover all banks once.
+// ---------------------------------------------------------------------------
+template <int W, bool KS>
+__device__ __forceinline__ uint32_t loader_src_offset(int chunk, int lane, int ld) {  // in bytes
+  const int pos = chunk * 1024 + lane * 16;
+  if (!KS) {
+    const int r = pos >> 7, q = (pos >> 4) & 7;
+    const int p = q ^ ((r >> 1) & 7);
+    return (uint32_t)(r * ld + p * 8) * 2u;
+  } else {
+    constexpr int RB = W * 2;
+    const int k = pos / RB, q = (pos % RB) >> 4;
+    const int p = q ^ ((k & 3) << 2);
+    return (uint32_t)(k * ld + p * 8) * 2u;
+  }
+}
+
+// a W x 64 (or 64 x W) tile is W/8 chunks of 1 KB; wave w moves chunks w, w + NW, ...
+template <int W, int NW>
+__device__ __forceinline__ void issue_tile_loads(const char* __restrict__ g, const uint32_t* off, char* __restrict__ lds, int wave) {
+#pragma unroll
+  for (int i = 0; i < W / 8 / NW; i++) load16_to_lds(g + off[i], lds + (wave + NW * i) * 1024);
+}
+
+// fragment (8 k-values for row/col = lane % 32 of a 32-wide block) for k-step ks (0..3)
+template <int W, bool KS>
+__device__ __forceinline__ bf16x8 read_frag(const char* __restrict__ lds, int base, int blk, int ks, int lane) {
+  if (!KS) {
+    const int r = base + blk * 32 + (lane & 31);
+    const int p = ks * 2 + (lane >> 5);
+    const int q = p ^ ((r >> 1) & 7);
+    return *(const bf16x8*)(lds + r * 128 + q * 16);
+  } else {
+    constexpr int RB = W * 2;
+    const int k = ks * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
+    const int c = base + blk * 32 + ((lane >> 4) & 1) * 16 + 4 * (lane & 3);
+    const int a0 = k * RB + ((((c >> 5) ^ (k & 3))) << 6) + ((c * 2) & 63);
+    bf16x4 lo = lds_read_tr4(lds + a0);
+    bf16x4 hi = lds_read_tr4(lds + a0 + 4 * RB);
+    return cat4(lo, hi);
+  }
+}
+
+// Fragments of one 16-wide k-step for the wave's sub-tile.
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+struct Frags {
+  static constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+  bf16x8 a[TM], b[TN];
+  __device__ __forceinline__ void load(const char* __restrict__ cA, const char* __restrict__ cB, int ks, int wm, int wn, int lane) {
+#pragma unroll
+    for (int t = 0; t < TM; t++) a[t] = read_frag<BM, AKS>(cA, wm * (BM / WGM), t, ks, lane);
+#pragma unroll
+    for (int t = 0; t < TN; t++) b[t] = read_frag<BN, BKS>(cB, wn * (BN / WGN), t, ks, lane);
+  }
+};
+
+// Scheduling hint for one k-step: between consecutive MFMAs (NM of them) place
+// the NV global->LDS loads and the NR LDS reads issued for later steps, the LDS
+// reads within the first three quarters so their latency is covered by the rest.
+// Masks: 0x020 = vector memory read, 0x100 = LDS read, 0x008 = MFMA.
+template <int I, int NM, int NR, int NV>
+__device__ __forceinline__ void interleave() {
+  if constexpr (I < NM) {
+    constexpr int SPAN = NM * 3 / 4 > 0 ? NM * 3 / 4 : 1;
+    constexpr int v = (I + 1) * NV / NM - I * NV / NM;
+    constexpr int r = I < SPAN ? (I + 1) * NR / SPAN - I * NR / SPAN : 0;
+    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
+    if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    interleave<I + 1, NM, NR, NV>();
+  }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+__device__ __forceinline__ void mma_step(const Frags<BM, BN, WGM, WGN, AKS, BKS>& f, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+#pragma unroll
+  for (int tm = 0; tm < TM; tm++)
+#pragma unroll
+    for (int tn = 0; tn < TN; tn++)
+      acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[tn], f.a[tm], acc[tm][tn], 0, 0, 0);
+}
+
+// The pipeline.  Operand tiles of 64 k are numbered A_0, B_0, A_1, B_1, ...; tile n lives in ring buffer n % 5.
+// A k-block (A_j, B_j) is four k-steps of 16; fragments are double-buffered in registers (f0, f1), the fragments
+// of a k-step being read from LDS under the MFMAs of the step before.  Each half of a k-block starts the loads of
+// one tile three tiles ahead, into the buffer of a tile of the previous k-block.  That buffer is free: the one
+// barrier per k-block (before the first fragments of the next k-block are read) is preceded by a wait for the
+// wave's own LDS reads, and after it no wave reads the finished k-block again.  The same wait counts the wave's
+// own loads down to the one tile issued last, so the next k-block has landed for the whole block.
+// (In the code below the tile sequence is F_0, S_0, F_1, ...: F is A or B, see b_first.)
+// The two halves are separate functions so that within each the buffer written is not one of the buffers read:
+// the restrict qualifiers then tell the compiler that LDS reads never wait for the loads in flight.
+
+// Which operand's tiles take the even numbers matters: an even tile is requested 2.5 half-blocks before its
+// first use, an odd one 1.5.  The weights (B of the forward and input-gradient products) stream from HBM while
+// the activations were just written and mostly sit in the caches, so there B goes first.
+template <bool AKS>
+constexpr bool b_first() { return !AKS; }
+
+// k-steps 0 and 1 of k-block j; on entry f0 holds the fragments of k-step 0.  Starts the loads of the odd tile
+// of k-block j+1.
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+__device__ __forceinline__ void half_even(const char* gS, const uint32_t* offS, char* __restrict__ fill, const char* __restrict__ cA,
+                                          const char* __restrict__ cB, Frags<BM, BN, WGM, WGN, AKS, BKS>& f0,
+                                          Frags<BM, BN, WGM, WGN, AKS, BKS>& f1, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32],
+                                          int wave, int wm, int wn, int lane) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
+  constexpr int NR = TM * (AKS ? 2 : 1) + TN * (BKS ? 2 : 1), NM = TM * TN;
+  constexpr int WS = b_first<AKS>() ? BM : BN;  // the odd tiles are A tiles when B goes first
+  issue_tile_loads<WS, NW>(gS, offS, fill, wave);
+  f1.load(cA, cB, 1, wm, wn, lane);
+  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
+  interleave<0, NM, NR, WS / 8 / NW>();
+  f0.load(cA, cB, 2, wm, wn, lane);
+  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
+  interleave<0, NM, NR, 0>();
+}
+
+// k-steps 2 and 3 of k-block j; on entry f0 holds the fragments of k-step 2.  Starts the loads of the even tile
+// of k-block j+2, waits for k-block j+1 (nA, nB) and leaves its first fragments in f0.
+template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+__device__ __forceinline__ void half_odd(const char* gF, const uint32_t* offF, char* __restrict__ fill, const char* __restrict__ cA,
+                                         const char* __restrict__ cB, const char* __restrict__ nA, const char* __restrict__ nB,
+                                         Frags<BM, BN, WGM, WGN, AKS, BKS>& f0, Frags<BM, BN, WGM, WGN, AKS, BKS>& f1,
+                                         f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], int wave, int wm, int wn, int lane) {
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
+  constexpr int NR = TM * (AKS ? 2 : 1) + TN * (BKS ? 2 : 1), NM = TM * TN;
+  constexpr int WF = b_first<AKS>() ? BN : BM;
+  issue_tile_loads<WF, NW>(gF, offF, fill, wave);
+  f1.load(cA, cB, 3, wm, wn, lane);
+  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
+  interleave<0, NM, NR, WF / 8 / NW>();
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(WF / 8 / NW));
+  __builtin_amdgcn_s_barrier();
+  f0.load(nA, nB, 0, wm, wn, lane);
+  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
+  interleave<0, NM, NR, 0>();
+}
+
+}  // namespace k64
+
+namespace k32 {
 constexpr int BK = 32;  // k-extent of one LDS stage (64 bytes of bf16)
 constexpr int NS = 4;   // stages in the LDS ring: loads run 3 stages ahead of the MFMAs
 
@@ -141,21 +304,16 @@ __device__ __forceinline__ void ring_step(const char* gA, const char* gB, const 
   interleave<0, NM, NR, 0>();
 }
 
+}  // namespace k32
+
 template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
-  constexpr int LPS = (BM + BN) / 16 / NW;
-  // ring slot t: A tile at t * SLOT, B tile behind it; the epilogue reuses the ring as staging space
-  constexpr int SLOT = (BM + BN) * 64;
-  __shared__ __attribute__((aligned(1024))) char ring[NS * SLOT];
-  char* const sA0 = ring;
-  char* const sB0 = ring + BM * 64;
-  char* const sA1 = ring + SLOT;
-  char* const sB1 = ring + SLOT + BM * 64;
-  char* const sA2 = ring + 2 * SLOT;
-  char* const sB2 = ring + 2 * SLOT + BM * 64;
-  char* const sA3 = ring + 3 * SLOT;
-  char* const sB3 = ring + 3 * SLOT + BM * 64;
+  constexpr bool K32 = AKS && BKS;                      // which pipeline
+  constexpr int BUF = (BM > BN ? BM : BN) * 128;        // k64: one ring buffer holds an A or a B tile
+  constexpr int RING = K32 ? k32::NS * (BM + BN) * 64 : k64::NB * BUF;
+  // the epilogue reuses the ring as staging space
+  __shared__ __attribute__((aligned(1024))) char ring[RING];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in scalar registers
@@ -178,15 +336,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 
   const char* gA = (const char*)((const bf16*)g.A + (AKS ? (size_t)m0 : (size_t)m0 * g.lda));
   const char* gB = (const char*)((const bf16*)g.B + (BKS ? (size_t)n0 : (size_t)n0 * g.ldb));
-  const size_t stepA = (AKS ? (size_t)BK * g.lda : (size_t)BK) * 2;  // bytes per stage
-  const size_t stepB = (BKS ? (size_t)BK * g.ldb : (size_t)BK) * 2;
-
-  uint32_t offA[BM / 16 / NW], offB[BN / 16 / NW];
-#pragma unroll
-  for (int i = 0; i < BM / 16 / NW; i++) offA[i] = loader_src_offset<BM, AKS>(wave + NW * i, lane, g.lda);
-#pragma unroll
-  for (int i = 0; i < BN / 16 / NW; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
-
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; i++)
@@ -195,29 +344,96 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
-  // nk is a multiple of 4 (K is a multiple of 128).  Stage t lives in ring slot t % 4.
-  const int nk = g.K / BK, last = nk - 1;
-  issue_tile_loads<BM, NW>(gA, offA, sA0, wave);
-  issue_tile_loads<BN, NW>(gB, offB, sB0, wave);
-  issue_tile_loads<BM, NW>(gA + stepA, offA, sA1, wave);
-  issue_tile_loads<BN, NW>(gB + stepB, offB, sB1, wave);
-  issue_tile_loads<BM, NW>(gA + 2 * stepA, offA, sA2, wave);
-  issue_tile_loads<BN, NW>(gB + 2 * stepB, offB, sB2, wave);
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
-  __builtin_amdgcn_s_barrier();
+  if constexpr (K32) {
+    using namespace k32;
+    constexpr int LPS = (BM + BN) / 16 / NW;
+    constexpr int SLOT = (BM + BN) * 64;  // ring slot t: A tile at t * SLOT, B tile behind it
+    char* const sA0 = ring;
+    char* const sB0 = ring + BM * 64;
+    char* const sA1 = ring + SLOT;
+    char* const sB1 = ring + SLOT + BM * 64;
+    char* const sA2 = ring + 2 * SLOT;
+    char* const sB2 = ring + 2 * SLOT + BM * 64;
+    char* const sA3 = ring + 3 * SLOT;
+    char* const sB3 = ring + 3 * SLOT + BM * 64;
+    const size_t stepA = (size_t)BK * g.lda * 2;  // bytes per stage (both operands k-strided)
+    const size_t stepB = (size_t)BK * g.ldb * 2;
+    uint32_t offA[BM / 16 / NW], offB[BN / 16 / NW];
+#pragma unroll
+    for (int i = 0; i < BM / 16 / NW; i++) offA[i] = loader_src_offset<BM, AKS>(wave + NW * i, lane, g.lda);
+#pragma unroll
+    for (int i = 0; i < BN / 16 / NW; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
+    // nk is a multiple of 4 (K is a multiple of 128).  Stage t lives in ring slot t % 4.
+    const int nk = g.K / BK, last = nk - 1;
+    issue_tile_loads<BM, NW>(gA, offA, sA0, wave);
+    issue_tile_loads<BN, NW>(gB, offB, sB0, wave);
+    issue_tile_loads<BM, NW>(gA + stepA, offA, sA1, wave);
+    issue_tile_loads<BN, NW>(gB + stepB, offB, sB1, wave);
+    issue_tile_loads<BM, NW>(gA + 2 * stepA, offA, sA2, wave);
+    issue_tile_loads<BN, NW>(gB + 2 * stepB, offB, sB2, wave);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+    __builtin_amdgcn_s_barrier();
 
-  Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
-  f0.load(sA0, sB0, 0, wm, wn, lane);
-  // The stage loaded during step t is min(t + 3, last): past the end the last stage is
-  // fetched again into a dead slot, which keeps the in-flight load count uniform.
+    Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
+    f0.load(sA0, sB0, 0, wm, wn, lane);
+    // The stage loaded during step t is min(t + 3, last): past the end the last stage is
+    // fetched again into a dead slot, which keeps the in-flight load count uniform.
 #define AH_STAGE_PTRS(t) gA + (size_t)min((t) + 3, last) * stepA, gB + (size_t)min((t) + 3, last) * stepB
-  for (int t = 0; t < nk; t += 4) {
-    ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t), offA, offB, sA3, sB3, sA0, sB0, sA1, sB1, f0, f1, acc, wave, wm, wn, lane);
-    ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 1), offA, offB, sA0, sB0, sA1, sB1, sA2, sB2, f0, f1, acc, wave, wm, wn, lane);
-    ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 2), offA, offB, sA1, sB1, sA2, sB2, sA3, sB3, f0, f1, acc, wave, wm, wn, lane);
-    ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 3), offA, offB, sA2, sB2, sA3, sB3, sA0, sB0, f0, f1, acc, wave, wm, wn, lane);
-  }
+    for (int t = 0; t < nk; t += 4) {
+      ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t), offA, offB, sA3, sB3, sA0, sB0, sA1, sB1, f0, f1, acc, wave, wm, wn, lane);
+      ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 1), offA, offB, sA0, sB0, sA1, sB1, sA2, sB2, f0, f1, acc, wave, wm, wn, lane);
+      ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 2), offA, offB, sA1, sB1, sA2, sB2, sA3, sB3, f0, f1, acc, wave, wm, wn, lane);
+      ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 3), offA, offB, sA2, sB2, sA3, sB3, sA0, sB0, f0, f1, acc, wave, wm, wn, lane);
+    }
 #undef AH_STAGE_PTRS
+  } else {
+    using namespace k64;
+    constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;     // loads per tile per wave
+    const size_t stepA = (AKS ? (size_t)BK * g.lda : (size_t)BK) * 2;  // bytes per k-block
+    const size_t stepB = (BKS ? (size_t)BK * g.ldb : (size_t)BK) * 2;
+
+    uint32_t offA[LA], offB[LB];
+#pragma unroll
+    for (int i = 0; i < LA; i++) offA[i] = loader_src_offset<BM, AKS>(wave + NW * i, lane, g.lda);
+#pragma unroll
+    for (int i = 0; i < LB; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
+
+    // K is a multiple of 128: an even number of k-blocks.  Past the end the last k-block is fetched again into
+    // dead buffers, which keeps the number of loads in flight uniform for the counted wait.
+    // F = the operand whose tiles take the even numbers, S = the other one.
+    constexpr bool BF = b_first<AKS>();
+    constexpr int WF = BF ? BN : BM, WS = BF ? BM : BN;
+    const char* gF = BF ? gB : gA;
+    const char* gS = BF ? gA : gB;
+    const size_t stepF = BF ? stepB : stepA, stepS = BF ? stepA : stepB;
+    const uint32_t* offF = BF ? offB : offA;
+    const uint32_t* offS = BF ? offA : offB;
+    const int np = g.K / BK, lastp = np - 1;
+    issue_tile_loads<WF, NW>(gF, offF, ring, wave);                                            // F_0 -> buffer 0
+    issue_tile_loads<WS, NW>(gS, offS, ring + BUF, wave);                                      // S_0 -> buffer 1
+    issue_tile_loads<WF, NW>(gF + (size_t)min(1, lastp) * stepF, offF, ring + 2 * BUF, wave);  // F_1 -> buffer 2
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(WF / 8 / NW));
+    __builtin_amdgcn_s_barrier();
+
+    Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
+    f0.load(ring + (BF ? BUF : 0), ring + (BF ? 0 : BUF), 0, wm, wn, lane);
+    int jf = 0, js = 1;  // buffers of F_j and S_j
+    for (int j = 0; j < np; j++) {
+      const int nf = jf + 2 >= NB ? jf + 2 - NB : jf + 2;  // F_{j+1}
+      const int ns = js + 2 >= NB ? js + 2 - NB : js + 2;  // S_{j+1}: loaded now, into the buffer of F_{j-1}
+      const int ff = jf + 4 >= NB ? jf + 4 - NB : jf + 4;  // F_{j+2}: into the buffer of S_{j-1}
+      const char* cA = ring + (BF ? js : jf) * BUF;
+      const char* cB = ring + (BF ? jf : js) * BUF;
+      const char* nA = ring + (BF ? ns : nf) * BUF;
+      const char* nB = ring + (BF ? nf : ns) * BUF;
+      half_even<BM, BN, WGM, WGN, AKS, BKS>(gS + (size_t)min(j + 1, lastp) * stepS, offS, ring + ns * BUF, cA, cB, f0, f1, acc, wave, wm, wn,
+                                            lane);
+      half_odd<BM, BN, WGM, WGN, AKS, BKS>(gF + (size_t)min(j + 2, lastp) * stepF, offF, ring + ff * BUF, cA, cB, nA, nB, f0, f1, acc, wave,
+                                           wm, wn, lane);
+      jf = nf;
+      js = ns;
+    }
+  }
   __builtin_amdgcn_s_waitcnt(0);  // drain the redundant tail loads before the block's LDS is released
 
   // ---- epilogue.  A lane holds C[m][n .. n+3] for 4 column groups of each 32x32 block: stores
@@ -226,7 +442,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   // back row-major, so that every global access is 16 bytes per lane and whole rows per 16 lanes.
   constexpr int WN = BN / WGN, WM = BM / WGM;
   constexpr int ROWB = WN * 4 + 16;                // padded strip row
-  static_assert(NW * 32 * ROWB <= NS * SLOT, "staging strips must fit in the ring");
+  static_assert(NW * 32 * ROWB <= RING, "staging strips must fit in the ring");
   __syncthreads();                                  // every wave is done with the ring
   char* strip = ring + wave * (32 * ROWB);
   const bf16* bias = (const bf16*)g.bias;
@@ -315,7 +531,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 }
 
 bool gemm_shape_ok(int M, int N, int K) {
-  return M > 0 && N > 0 && K > 0 && (M % 128) == 0 && (N % 128) == 0 && (K % (NS * BK)) == 0;
+  return M > 0 && N > 0 && K > 0 && (M % 128) == 0 && (N % 128) == 0 && (K % 128) == 0;
 }
 
 namespace {
