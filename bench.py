@@ -69,7 +69,12 @@ def main():
     ap.add_argument("--workload", default="gpt7b_tp2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--trace-steps", type=int, default=2)
+    ap.add_argument("--no-side-stream", action="store_true",
+                    help="keep all of backward on one stream, as the per-site trace does: kernel durations in a profile are then "
+                         "those of kernels that own the chip (the timed figure is ~1 %% lower)")
     args = ap.parse_args()
+    if args.no_side_stream:
+        os.environ["AH_NO_SIDE_STREAM"] = "1"
     if args.gpus != 1:
         print("bench.py measures one GPU's stage; this build has no multi-GPU path (--gpus %d refused)" % args.gpus, file=sys.stderr)
         sys.exit(2)
