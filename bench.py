@@ -6,6 +6,10 @@ and a backward pass through all layers, gradients accumulated in fp32 (restarted
 at micro-batch 0).  Workload: the 7B-class TP=2 shard (4 layers, hidden 4096,
 16 local heads x 128, local FFN 8192, seq 2048, micro-batch 2, K = 8), synthetic
 seeded data already resident in HBM.  Prints one JSON line.
+
+The weight-gradient products are deferred by default (--wgrad-group, default K): each layer's four products run
+once per step over the K micro-batches' tokens instead of once per micro-batch, all inside the timed step;
+--wgrad-group 1 gives the per-micro-batch accumulation.
 """
 import argparse
 import json
@@ -72,6 +76,9 @@ def main():
     ap.add_argument("--no-side-stream", action="store_true",
                     help="keep all of backward on one stream, as the per-site trace does: kernel durations in a profile are then "
                          "those of kernels that own the chip (the timed figure is ~1 %% lower)")
+    ap.add_argument("--wgrad-group", type=int, default=0,
+                    help="micro-batches per weight-gradient product (ah_stage_config_t.wgrad_group); 0 = all K of a step "
+                         "(1 with activation recomputation, which cannot defer)")
     args = ap.parse_args()
     if args.no_side_stream:
         os.environ["AH_NO_SIDE_STREAM"] = "1"
@@ -86,9 +93,10 @@ def main():
     w = SI.WORKLOADS[args.workload]
     torch.manual_seed(SI.BASE_SEED)
     dev = torch.device("cuda:0")
+    G = args.wgrad_group if args.wgrad_group > 0 else (1 if w["recompute"] else min(w["n_mb"], 16))
     cfg = P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
                              head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
-                             max_in_flight=1, recompute=w["recompute"])
+                             max_in_flight=G, recompute=w["recompute"], wgrad_group=G)
     st = P.Stage(cfg, device=dev)
     # synthetic weights of the stated distribution, generated on the device: N(0, 0.02), gains 1, biases 0
     st.params.normal_(0.0, 0.02)
@@ -107,8 +115,9 @@ def main():
     def step():
         st.zero_grads(stream)
         for m in range(K):
-            st.forward(0, xs[m], y, stream)
-            st.backward(0, dys[m], dx, stream)
+            st.forward(m % G, xs[m], y, stream)
+            st.backward(m % G, dys[m], dx, stream)
+        st.flush_grads(stream)   # an incomplete last group (K not a multiple of G); otherwise nothing is pending
 
     for _ in range(args.warmup):
         step()
@@ -156,9 +165,9 @@ def main():
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.md" % args.workload)
     if os.path.exists(tpath) and any(n.startswith("gemm_tn.fc") for n in dom["names"]):
-        for line in open(tpath):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = float(line.split(":")[1])   # fetch + write bytes of this kernel from the rocprofv3 counter runs
+        meta = dict(l.split(":", 1) for l in open(tpath) if l.startswith(("traffic_bytes_per_launch:", "wgrad_group:")))
+        if int(meta.get("wgrad_group", -1)) == G:   # the counter runs cover this launch shape only
+            traffic = float(meta["traffic_bytes_per_launch"])   # fetch + write bytes of this kernel from the rocprofv3 counter runs
     roofline = {"bound": "mfma", "kernel": "+".join(dom["names"]), "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "avg_launch_us": avg_ms * 1e3,
                 "launches": dom["launches"], "flops_per_launch": dom["flops_per_launch"]}
@@ -171,7 +180,7 @@ def main():
            "config": {"workload": args.workload, "arch": w["arch"], "layers": w["n_layers"], "hidden": w["hidden"],
                       "local_heads": w["n_heads"] // w["tp"], "head_dim": w["head_dim"], "local_ffn": w["ffn"] // w["tp"],
                       "seq_len": w["seq"], "microbatch": w["mb"], "microbatches": K, "tokens_per_step": tokens,
-                      "tp_degree": w["tp"], "recompute": w["recompute"], "parallelism": "1 GPU (one TP shard of one stage)"},
+                      "tp_degree": w["tp"], "recompute": w["recompute"], "wgrad_group": G, "parallelism": "1 GPU (one TP shard of one stage)"},
            "roofline": roofline,
            "sites": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in s.items()} for s in sites]}
     if not args.no_cpu_baseline:

@@ -89,6 +89,14 @@ typedef struct {
   int32_t n_microbatches;   /* K of Eq. 1: micro-batches accumulated per iteration (used by ah_stage_profile) */
   int32_t max_in_flight;    /* activation slots: micro-batches whose forward has run and whose backward has not (1F1B: stages - stage index) */
   int32_t recompute;        /* 0: keep every layer's activations; 1: keep layer inputs only and re-run each layer's forward inside backward */
+  int32_t wgrad_group;      /* G.  0 or 1: every ah_stage_backward adds its micro-batch's weight gradients at once.
+                             * G > 1 (<= 16, <= max_in_flight, recompute == 0): the weight-gradient products of a
+                             * layer are taken once per G micro-batches, over the concatenation of their tokens,
+                             * by the G-th backward of each group (or ah_stage_flush_grads): the fp32 gradient
+                             * matrices are then read and written once per group instead of once per micro-batch.
+                             * The sums are the same up to fp32 rounding order.  Cost: a micro-batch's slot stays
+                             * occupied until its group is taken, and the workspace holds G * n_layers blocks of
+                             * output-gradient operands (2*T*(2*hidden + first-MLP width + 3*local attention width) bytes each). */
   float norm_eps;           /* 0 selects the default: 1e-5 (GPT), 1e-6 (LLaMA) */
   float rope_base;          /* 0 selects 10000 */
 } ah_stage_config_t;
@@ -98,7 +106,7 @@ typedef struct {
   uint64_t param_bytes, grad_bytes;   /* 2 and 4 bytes per element */
   uint64_t activation_bytes_per_slot; /* saved for backward, per in-flight micro-batch */
   uint64_t activation_bytes_per_layer_per_slot;
-  uint64_t workspace_bytes;           /* scratch shared by all slots */
+  uint64_t workspace_bytes;           /* scratch shared by all slots (includes the pending blocks of wgrad_group > 1) */
 } ah_stage_sizes_t;
 
 /* Device buffers, caller-owned, 256-byte aligned, of at least the sizes
@@ -147,16 +155,29 @@ int ah_stage_forward(ah_stage_t* st, int slot, const void* x, void* y, void* hip
  * of t_i^j).  dy: device bf16 [B*S, hidden], read only; dx: device bf16
  * [B*S, hidden], written.  Adds every parameter's gradient into the fp32
  * gradient buffer (plain sum over micro-batches, no 1/K), or overwrites it if
- * this is the first backward after ah_stage_zero_grads.  Frees the slot. */
+ * this is the first backward after ah_stage_zero_grads, and frees the slot.
+ * With wgrad_group G > 1 only the vector gradients (biases, gains, offsets) are
+ * added at once; the slot stays occupied, and the matrices' gradients follow
+ * when the G-th micro-batch of the group has had its backward (that call takes
+ * them for the whole group and frees all G slots) or at ah_stage_flush_grads. */
 int ah_stage_backward(ah_stage_t* st, int slot, const void* dy, void* dx, void* hip_stream);
 
+/* Takes the weight gradients of the micro-batches whose backward has run but
+ * whose group is incomplete (wgrad_group > 1 and a micro-batch count that is
+ * not a multiple of it), on `hip_stream`, and frees their slots.  After it the
+ * gradient buffer holds the full sums, in stream order.  No-op when nothing
+ * is pending. */
+int ah_stage_flush_grads(ah_stage_t* st, void* hip_stream);
+
 /* The fp32 gradient buffer (device pointer into the caller's `grads`) and its
- * element count; layout per ah_stage_param_layout. */
+ * element count; layout per ah_stage_param_layout.  With wgrad_group > 1 the
+ * matrices are complete once every group has been taken (see above). */
 int ah_stage_grads(ah_stage_t* st, float** dev_ptr, uint64_t* n_elems);
 
 /* Starts a new accumulation: the next ah_stage_backward overwrites instead of
  * adding (no memset is enqueued; until that backward has run the buffer holds
- * the previous iteration's sums).  A new stage starts in this state. */
+ * the previous iteration's sums).  A new stage starts in this state.
+ * AH_ESTATE while weight gradients are pending. */
 int ah_stage_zero_grads(ah_stage_t* st, void* hip_stream);
 
 /* Measures the stage on synthetic activations (what the paper's profiler
@@ -194,6 +215,12 @@ int ah_gemm_nn(const void* A, const void* B, const void* bias, void* C, int M, i
 int ah_gemm_nt(const void* A, const void* B, void* C, int M, int N, int K, void* hip_stream);
 /* C[M,N] (fp32) = beta * C + A[K,M]^T B[K,N], beta in {0, 1}.  Same constraints. */
 int ah_gemm_tn(const void* A, const void* B, float* C, int M, int N, int K, int beta, void* hip_stream);
+/* ah_gemm_tn with the k axis given in n_seg pieces of seg_k rows each (K = n_seg * seg_k): piece i of A is
+ * A_seg[i][seg_k, M], of B is B_seg[i][seg_k, N].  A_seg and B_seg are HOST arrays of device pointers, read
+ * during the call.  1 <= n_seg <= 16, seg_k a multiple of 128.  This is the product the deferred weight
+ * gradient (wgrad_group) runs over the micro-batches of a group. */
+int ah_gemm_tn_segmented(const void* const* A_seg, const void* const* B_seg, int n_seg, float* C, int M, int N, int seg_k,
+                         int beta, void* hip_stream);
 /* Attention over packed qkv[B*S, 3*nh*d] (bf16, [Q|K|V], head-major): o[B*S, nh*d] bf16, lse[B, nh, S] fp32.
  * causal != 0: query i attends to keys 0..i of its sequence; causal == 0: to all S keys. */
 int ah_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, int causal, void* hip_stream);

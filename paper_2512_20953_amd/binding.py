@@ -28,13 +28,13 @@ class StageConfig(C.Structure):
                 ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn_hidden", C.c_int32), ("tp_degree", C.c_int32),
                 ("tp_rank", C.c_int32), ("seq_len", C.c_int32), ("microbatch_size", C.c_int32),
                 ("n_microbatches", C.c_int32), ("max_in_flight", C.c_int32), ("recompute", C.c_int32),
-                ("norm_eps", C.c_float), ("rope_base", C.c_float)]
+                ("wgrad_group", C.c_int32), ("norm_eps", C.c_float), ("rope_base", C.c_float)]
 
     @classmethod
     def make(cls, arch="gpt", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=1024, tp=1, tp_rank=0, seq=128, mb=1,
-             n_mb=1, max_in_flight=1, recompute=0, norm_eps=0.0, rope_base=0.0):
+             n_mb=1, max_in_flight=1, recompute=0, wgrad_group=0, norm_eps=0.0, rope_base=0.0):
         return cls(C.sizeof(cls), _ARCH[arch], n_layers, hidden, n_heads, head_dim,
-                   ffn, tp, tp_rank, seq, mb, n_mb, max_in_flight, recompute, norm_eps, rope_base)
+                   ffn, tp, tp_rank, seq, mb, n_mb, max_in_flight, recompute, wgrad_group, norm_eps, rope_base)
 
 
 class _Sizes(C.Structure):
@@ -83,6 +83,7 @@ def _load():
     L.ah_stage_backward.argtypes = [vp, i, vp, vp, vp]
     L.ah_stage_grads.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_uint64)]
     L.ah_stage_zero_grads.argtypes = [vp, vp]
+    L.ah_stage_flush_grads.argtypes = [vp, vp]
     L.ah_stage_profile.argtypes = [vp, i, i, C.POINTER(_Profile)]
     L.ah_stage_trace_begin.argtypes = [vp]
     L.ah_stage_trace_end.argtypes = [vp, C.POINTER(_TraceEntry), i, C.POINTER(i)]
@@ -95,6 +96,7 @@ def _load():
     L.ah_gemm_nn.argtypes = [vp, vp, vp, vp, i, i, i, vp]
     L.ah_gemm_nt.argtypes = [vp, vp, vp, i, i, i, vp]
     L.ah_gemm_tn.argtypes = [vp, vp, vp, i, i, i, i, vp]
+    L.ah_gemm_tn_segmented.argtypes = [C.POINTER(vp), C.POINTER(vp), i, vp, i, i, i, i, vp]
     L.ah_attention_fwd.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
     L.ah_attention_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
     return L
@@ -175,6 +177,9 @@ class Stage:
     def zero_grads(self, stream=None):
         _check(lib.ah_stage_zero_grads(self._h, _stream(stream)))
 
+    def flush_grads(self, stream=None):
+        _check(lib.ah_stage_flush_grads(self._h, _stream(stream)))
+
     def grads_ptr(self):
         p, n = C.c_void_p(), C.c_uint64()
         _check(lib.ah_stage_grads(self._h, C.byref(p), C.byref(n)))
@@ -215,6 +220,14 @@ def gemm_nt(A, B, Cout, stream=None):
 def gemm_tn(A, B, Cout, beta, stream=None):
     K, M = A.shape
     _check(lib.ah_gemm_tn(_ptr(A), _ptr(B), _ptr(Cout), M, B.shape[1], K, int(beta), _stream(stream)))
+
+
+def gemm_tn_segmented(A_list, B_list, Cout, beta, stream=None):
+    n = len(A_list)
+    seg_k, M = A_list[0].shape
+    pa = (C.c_void_p * n)(*[a.data_ptr() for a in A_list])
+    pb = (C.c_void_p * n)(*[b.data_ptr() for b in B_list])
+    _check(lib.ah_gemm_tn_segmented(pa, pb, n, _ptr(Cout), M, B_list[0].shape[1], seg_k, int(beta), _stream(stream)))
 
 
 def attention_fwd(qkv, o, lse, B, S, nh, d, causal=True, stream=None):

@@ -37,3 +37,22 @@ extern "C" int ah_gemm_tn(const void* A, const void* B, float* C, int M, int N, 
   g.lda = M; g.ldb = N; g.ldc = N; g.M = M; g.N = N; g.K = K; g.beta = beta;
   return hip_status(launch_gemm(GEMM_TN, EPI_F32_ACC, g, (hipStream_t)stream), "ah_gemm_tn");
 }
+
+extern "C" int ah_gemm_tn_segmented(const void* const* A_seg, const void* const* B_seg, int n_seg, float* C, int M, int N, int seg_k,
+                                    int beta, void* stream) {
+  discard_stale_hip_error();
+  if (!A_seg || !B_seg || !C) return set_error(AH_EINVAL, "ah_gemm_tn_segmented: NULL pointer");
+  if (beta != 0 && beta != 1) return set_error(AH_EINVAL, "ah_gemm_tn_segmented: beta must be 0 or 1");
+  if (!gemm_segments_ok(seg_k, n_seg)) return set_error(AH_EUNSUPPORTED, "ah_gemm_tn_segmented: need 1 <= n_seg <= %d pieces of seg_k %% 128 == 0 rows", kMaxGemmSegments);
+  if (!gemm_shape_ok(M, N, seg_k * n_seg)) return set_error(AH_EUNSUPPORTED, "ah_gemm_tn_segmented: %s", kShapeMsg);
+  GemmArgs g = {};
+  for (int i = 0; i < n_seg; i++) {
+    if (!A_seg[i] || !B_seg[i]) return set_error(AH_EINVAL, "ah_gemm_tn_segmented: piece %d is NULL", i);
+    g.segA[i] = A_seg[i];
+    g.segB[i] = B_seg[i];
+  }
+  g.A = A_seg[0]; g.B = B_seg[0]; g.C = C;
+  g.seg_k = seg_k; g.n_seg = n_seg;
+  g.lda = M; g.ldb = N; g.ldc = N; g.M = M; g.N = N; g.K = seg_k * n_seg; g.beta = beta;
+  return hip_status(launch_gemm(GEMM_TN, EPI_F32_ACC, g, (hipStream_t)stream), "ah_gemm_tn_segmented");
+}

@@ -365,27 +365,51 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     for (int i = 0; i < BN / 16 / NW; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
     // nk is a multiple of 4 (K is a multiple of 128).  Stage t lives in ring slot t % 4.
     const int nk = g.K / BK, last = nk - 1;
-    issue_tile_loads<BM, NW>(gA, offA, sA0, wave);
-    issue_tile_loads<BN, NW>(gB, offB, sB0, wave);
-    issue_tile_loads<BM, NW>(gA + stepA, offA, sA1, wave);
-    issue_tile_loads<BN, NW>(gB + stepB, offB, sB1, wave);
-    issue_tile_loads<BM, NW>(gA + 2 * stepA, offA, sA2, wave);
-    issue_tile_loads<BN, NW>(gB + 2 * stepB, offB, sB2, wave);
+    // The k axis may be cut into pieces that live in different buffers (kernels.h).  (pA, pB) is the stage to be
+    // fetched next; it walks through a piece by stepA / stepB and jumps to the next piece's base at its end.
+    // Past the last stage it stays put: the last stage is fetched again into a dead slot, which keeps the
+    // in-flight load count uniform.  All of this is wave-uniform scalar arithmetic.
+    const int seg_stages = g.n_seg > 0 ? g.seg_k / BK : nk;
+    const char *pA = gA, *pB = gB;
+    int q = 0, within = 0, seg = 0;
+    auto advance = [&]() {
+      if (q >= last) return;
+      q++;
+      if (++within == seg_stages) {
+        within = 0;
+        seg++;
+        pA = (const char*)((const bf16*)g.segA[seg] + m0);
+        pB = (const char*)((const bf16*)g.segB[seg] + n0);
+      } else {
+        pA += stepA;
+        pB += stepB;
+      }
+    };
+    issue_tile_loads<BM, NW>(pA, offA, sA0, wave);
+    issue_tile_loads<BN, NW>(pB, offB, sB0, wave);
+    advance();
+    issue_tile_loads<BM, NW>(pA, offA, sA1, wave);
+    issue_tile_loads<BN, NW>(pB, offB, sB1, wave);
+    advance();
+    issue_tile_loads<BM, NW>(pA, offA, sA2, wave);
+    issue_tile_loads<BN, NW>(pB, offB, sB2, wave);
+    advance();
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
     __builtin_amdgcn_s_barrier();
 
     Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
     f0.load(sA0, sB0, 0, wm, wn, lane);
-    // The stage loaded during step t is min(t + 3, last): past the end the last stage is
-    // fetched again into a dead slot, which keeps the in-flight load count uniform.
-#define AH_STAGE_PTRS(t) gA + (size_t)min((t) + 3, last) * stepA, gB + (size_t)min((t) + 3, last) * stepB
+    // the stage loaded during step t is min(t + 3, last)
     for (int t = 0; t < nk; t += 4) {
-      ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t), offA, offB, sA3, sB3, sA0, sB0, sA1, sB1, f0, f1, acc, wave, wm, wn, lane);
-      ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 1), offA, offB, sA0, sB0, sA1, sB1, sA2, sB2, f0, f1, acc, wave, wm, wn, lane);
-      ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 2), offA, offB, sA1, sB1, sA2, sB2, sA3, sB3, f0, f1, acc, wave, wm, wn, lane);
-      ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 3), offA, offB, sA2, sB2, sA3, sB3, sA0, sB0, f0, f1, acc, wave, wm, wn, lane);
+      ring_step<BM, BN, WGM, WGN, AKS, BKS>(pA, pB, offA, offB, sA3, sB3, sA0, sB0, sA1, sB1, f0, f1, acc, wave, wm, wn, lane);
+      advance();
+      ring_step<BM, BN, WGM, WGN, AKS, BKS>(pA, pB, offA, offB, sA0, sB0, sA1, sB1, sA2, sB2, f0, f1, acc, wave, wm, wn, lane);
+      advance();
+      ring_step<BM, BN, WGM, WGN, AKS, BKS>(pA, pB, offA, offB, sA1, sB1, sA2, sB2, sA3, sB3, f0, f1, acc, wave, wm, wn, lane);
+      advance();
+      ring_step<BM, BN, WGM, WGN, AKS, BKS>(pA, pB, offA, offB, sA2, sB2, sA3, sB3, sA0, sB0, f0, f1, acc, wave, wm, wn, lane);
+      advance();
     }
-#undef AH_STAGE_PTRS
   } else {
     using namespace k64;
     constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;     // loads per tile per wave
@@ -534,6 +558,10 @@ bool gemm_shape_ok(int M, int N, int K) {
   return M > 0 && N > 0 && K > 0 && (M % 128) == 0 && (N % 128) == 0 && (K % 128) == 0;
 }
 
+bool gemm_segments_ok(int seg_k, int n_seg) {
+  return seg_k > 0 && (seg_k % 128) == 0 && n_seg >= 1 && n_seg <= kMaxGemmSegments && (long)seg_k * n_seg <= (1L << 30);
+}
+
 namespace {
 
 // Tile choice: the 256-CU chip runs one block per CU, so a launch costs
@@ -592,6 +620,13 @@ hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in
   if (grp < 0) { grp = getenv("AH_GEMM_GROUP") ? atoi(getenv("AH_GEMM_GROUP")) : 8; remap = getenv("AH_GEMM_NOREMAP") ? 0 : 1; }
   a.group = grp; a.xcd_remap = remap;
   if (!gemm_shape_ok(a.M, a.N, a.K)) return hipErrorInvalidValue;
+  if (a.n_seg != 0) {  // pieces along k: weight-gradient layout only, and the pieces must add up to K
+    if (layout != GEMM_TN || !gemm_segments_ok(a.seg_k, a.n_seg) || (long)a.seg_k * a.n_seg != a.K) return hipErrorInvalidValue;
+    for (int i = 0; i < a.n_seg; i++)
+      if (!a.segA[i] || !a.segB[i]) return hipErrorInvalidValue;
+    a.A = a.segA[0];
+    a.B = a.segB[0];
+  }
   const int t = pick_tile(a.M, a.N, layout == GEMM_TN);
   if (t < 0) return hipErrorInvalidValue;
   if (layout == GEMM_NN) {

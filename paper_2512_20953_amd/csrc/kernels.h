@@ -15,6 +15,8 @@ enum GemmEpilogue {
   EPI_F32_SET = 5    // C (fp32) = acc            (internal: EPI_F32_ACC with beta == 0)
 };
 
+constexpr int kMaxGemmSegments = 16;
+
 struct GemmArgs {
   const void* A;     // NN/NT: [M, K] row-major;  TN: [K, M] row-major
   const void* B;     // NN/TN: [K, N] row-major;  NT: [N, K] row-major
@@ -26,11 +28,17 @@ struct GemmArgs {
   int M, N, K;
   int beta;
   int group, xcd_remap;  // tile rasterisation (set by launch_gemm)
+  // TN only: the k axis may be the concatenation of n_seg pieces of seg_k rows each (K = n_seg * seg_k), piece i
+  // of A starting at segA[i] and of B at segB[i] (same leading dimensions).  n_seg == 0: one piece, A and B.
+  int seg_k, n_seg;
+  const void* segA[kMaxGemmSegments];
+  const void* segB[kMaxGemmSegments];
 };
 
 // M, N, K multiples of 128, all leading dimensions multiples of 8.
 hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, hipStream_t s);
 bool gemm_shape_ok(int M, int N, int K);
+bool gemm_segments_ok(int seg_k, int n_seg);  // seg_k a positive multiple of 128, 1 <= n_seg <= kMaxGemmSegments
 
 // ---- attention (d = 64 or 128, S multiple of 128) ----
 // causal: query i attends to keys 0..i of its sequence; otherwise to all S keys

@@ -28,8 +28,12 @@ struct ActLayout {
 };
 
 struct Workspace {
-  size_t d0, d1, dmid, dbig, dsm, delta, part_n2, part_n1, part_b1, part_bqkv, rope, prof_x, prof_dy, prof_y, prof_dx, layer_ws, bytes;
+  size_t d0, d1, dmid, dbig, dsm, delta, part_n2, part_n1, part_b1, part_bqkv, rope, prof_x, prof_dy, prof_y, prof_dx, layer_ws, pend, bytes;
 };
+
+// Output-gradient operands of one layer's four weight-gradient products, kept per (position in the group, layer)
+// while those products wait for the rest of the group: byte offsets inside one such block.
+struct PendLayout { size_t dy, dmid, du, dqkv, bytes; };
 
 }  // namespace
 
@@ -45,8 +49,15 @@ struct ah_stage {
   size_t slot_bytes;   // per in-flight micro-batch
   size_t per_layer_slot_bytes;
   Workspace ws;
-  std::vector<char> busy;
-  bool overwrite_grads;  // next backward writes instead of adding
+  std::vector<char> busy;  // per slot: 0 empty, 1 forward done, 2 backward done and weight gradients pending
+  bool overwrite_grads;   // next backward writes the vector gradients (and, undeferred, the matrices) instead of adding
+  bool overwrite_wgrads;  // next weight-gradient product writes instead of adding
+  // Deferred weight gradients: with group > 1 the four weight-gradient products of a layer run once per `group`
+  // micro-batches, over the concatenation of their tokens, instead of once per micro-batch.
+  int group;
+  bool force_immediate;         // the profiler's per-layer timing runs undeferred
+  PendLayout pend;
+  std::vector<int> pend_slots;  // slots of the micro-batches waiting, in backward order
   bool rope_ready;
   // optional per-call-site timing (ah_stage_trace_begin / _end)
   bool tracing;
@@ -57,6 +68,7 @@ struct ah_stage {
   bool side_ready, side_off;
   std::vector<hipEvent_t> ev_pool;           // pairs, in launch order
   std::vector<int> ev_site;                  // site of pair i
+  std::vector<int> ev_mult;                  // micro-batches covered by the launch of pair i
   size_t ev_used;
 };
 
@@ -74,6 +86,9 @@ int validate(const ah_stage_config_t* c) {
   if (c->n_microbatches < 1) return set_error(AH_EINVAL, "n_microbatches must be >= 1");
   if (c->max_in_flight < 1 || c->max_in_flight > 4096) return set_error(AH_EINVAL, "max_in_flight %d out of range [1, 4096]", c->max_in_flight);
   if (c->recompute != 0 && c->recompute != 1) return set_error(AH_EINVAL, "recompute must be 0 or 1");
+  if (c->wgrad_group < 0 || c->wgrad_group > kMaxGemmSegments) return set_error(AH_EINVAL, "wgrad_group %d out of range [0, %d]", c->wgrad_group, kMaxGemmSegments);
+  if (c->wgrad_group > 1 && c->recompute) return set_error(AH_EINVAL, "wgrad_group > 1 keeps activations for the deferred products: recompute must be 0");
+  if (c->wgrad_group > c->max_in_flight) return set_error(AH_EINVAL, "wgrad_group %d needs max_in_flight >= %d (a slot stays occupied until its group's weight gradients are taken)", c->wgrad_group, c->wgrad_group);
   if (c->norm_eps < 0 || c->rope_base < 0) return set_error(AH_EINVAL, "norm_eps and rope_base must be >= 0");
   if (c->head_dim != 64 && c->head_dim != 128) return set_error(AH_EUNSUPPORTED, "head_dim %d: only 64 and 128 are supported", c->head_dim);
   if (c->hidden % 128 || c->hidden > 16384) return set_error(AH_EUNSUPPORTED, "hidden %d must be a multiple of 128 and <= 16384", c->hidden);
@@ -97,6 +112,7 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
   s->llama = c->arch == AH_ARCH_LLAMA;
   s->causal = c->arch != AH_ARCH_BERT;
   s->recompute = c->recompute != 0;
+  s->group = c->wgrad_group > 1 ? c->wgrad_group : 1;
   s->eps = c->norm_eps > 0 ? c->norm_eps : (s->llama ? 1e-6f : 1e-5f);
   s->rope_base = c->rope_base > 0 ? c->rope_base : 10000.f;
   const int h = s->h, hl = s->hl, F = s->F;
@@ -160,6 +176,15 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
   w.prof_y = take(T * h * 2);
   w.prof_dx = take(T * h * 2);
   w.layer_ws = take(s->recompute ? a.bytes : 0);
+  const size_t before_pend = o;
+  o = 0;
+  s->pend.dy = take(T * h * 2);
+  s->pend.dmid = take(T * h * 2);
+  s->pend.du = take(T * Fu * 2);
+  s->pend.dqkv = take(T * 3 * hl * 2);
+  s->pend.bytes = o;
+  o = before_pend;
+  w.pend = take(s->group > 1 ? (size_t)s->group * s->L * s->pend.bytes : 0);
   w.bytes = o;
 }
 
@@ -200,7 +225,7 @@ struct SiteTimer {
   ah_stage* s;
   hipStream_t st;
   size_t slot;
-  SiteTimer(ah_stage* s_, int site, hipStream_t st_) : s(s_), st(st_), slot((size_t)-1) {
+  SiteTimer(ah_stage* s_, int site, hipStream_t st_, int mult = 1) : s(s_), st(st_), slot((size_t)-1) {
     if (!s->tracing) return;
     if (s->ev_used + 2 > s->ev_pool.size()) {
       hipEvent_t a, b;
@@ -209,8 +234,10 @@ struct SiteTimer {
       s->ev_pool.push_back(a);
       s->ev_pool.push_back(b);
       s->ev_site.push_back(site);
+      s->ev_mult.push_back(mult);
     } else {
       s->ev_site[s->ev_used / 2] = site;
+      s->ev_mult[s->ev_used / 2] = mult;
     }
     slot = s->ev_used;
     s->ev_used += 2;
@@ -280,6 +307,44 @@ hipError_t gemm(ah_stage* s, int site, GemmLayout lay, GemmEpilogue epi, const v
   return launch_gemm(lay, epi, g, st);
 }
 
+// buffers one layer's backward writes its intermediate gradients to
+struct BwdBufs { char *dmid, *du, *dqkv; };
+
+BwdBufs pend_bufs(const ah_stage* s, int pos, int layer, char** dy_out) {
+  char* b = (char*)s->bufs.workspace + s->ws.pend + ((size_t)pos * s->L + layer) * s->pend.bytes;
+  if (dy_out) *dy_out = b + s->pend.dy;
+  return {b + s->pend.dmid, b + s->pend.du, b + s->pend.dqkv};
+}
+
+// What a layer's backward does about its four weight-gradient products.
+//   nseg == 0: takes them now, over this micro-batch alone (operands: this slot's activations and the BwdBufs);
+//   nseg <  0: leaves them to a later call;
+//   nseg >  0: takes them over the nseg micro-batches in slots[] (group positions 0 .. nseg - 1), whose token
+//              axes are concatenated inside the product.
+struct WgradPlan { int nseg; int slots[kMaxGemmSegments]; int beta; };
+
+enum WgradWhich { WG_FC2, WG_FC1, WG_WO, WG_QKV };
+
+// One weight-gradient product C[M, N] (+)= sum over the plan's micro-batches of act^T dY.
+hipError_t wgrad(ah_stage* s, int site, int layer, WgradWhich which, const WgradPlan& wp, const void* act, const void* dY, float* C,
+                 int M, int N, hipStream_t st) {
+  GemmArgs g = {};
+  g.A = act; g.B = dY; g.C = C;
+  g.lda = M; g.ldb = N; g.ldc = N; g.M = M; g.N = N; g.K = s->T; g.beta = wp.beta;
+  if (wp.nseg > 0) {
+    g.seg_k = s->T; g.n_seg = wp.nseg; g.K = s->T * wp.nseg;
+    for (int i = 0; i < wp.nseg; i++) {
+      const ActPtrs a = act_ptrs(s, wp.slots[i], layer);
+      char* dy;
+      const BwdBufs b = pend_bufs(s, i, layer, &dy);
+      g.segA[i] = which == WG_FC2 ? a.g : which == WG_FC1 ? a.c : which == WG_WO ? a.o : a.a;
+      g.segB[i] = which == WG_FC2 ? dy : which == WG_FC1 ? b.du : which == WG_WO ? b.dmid : b.dqkv;
+    }
+  }
+  SiteTimer t(s, site, st, wp.nseg > 0 ? wp.nseg : 1);
+  return launch_gemm(GEMM_TN, EPI_F32_ACC, g, st);
+}
+
 // One layer forward.  y == nullptr: stop after the activations backward needs
 // (used when a layer is re-run inside backward).
 hipError_t layer_forward(ah_stage* s, int layer, const ActPtrs& a, void* y, hipStream_t st) {
@@ -314,16 +379,19 @@ hipError_t stream_order(hipStream_t from, hipStream_t to, hipEvent_t ev) {
 // after its producer on st, st waits for the side stream before a buffer the side stream still reads is
 // rewritten (dbig, by attention backward) and at the end of the layer (workspace and, with recompute, the
 // shared activation working set are reused by the next layer).
-hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, int beta, hipStream_t st, hipStream_t sd) {
+hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, int beta, const BwdBufs& bb,
+                          const WgradPlan& wp, hipStream_t st, hipStream_t sd) {
   const LayerPtrs p = layer_ptrs(s, layer);
   const int T = s->T, h = s->h, hl = s->hl, F = s->F, B = s->cfg.microbatch_size, S = s->cfg.seq_len;
+  const int Fu = s->llama ? 2 * F : F;
   char* wsb = (char*)s->bufs.workspace;
-  char *dmid = wsb + s->ws.dmid, *dbig = wsb + s->ws.dbig, *dsm = wsb + s->ws.dsm;
+  char *dmid = bb.dmid, *du = bb.du, *dqkv = bb.dqkv, *dsm = wsb + s->ws.dsm;
   float *part_n2 = (float*)(wsb + s->ws.part_n2), *part_n1 = (float*)(wsb + s->ws.part_n1);
   float *part_b1 = (float*)(wsb + s->ws.part_b1), *part_bqkv = (float*)(wsb + s->ws.part_bqkv);
   float* delta = (float*)(wsb + s->ws.delta);
   const int nb = norm_bwd_blocks(T), cb = colsum_blocks(T);
   const bool rms = s->llama;
+  const bool take_w = wp.nseg >= 0;
   hipEvent_t* ev = s->sync_ev;
 #define ON_SIDE(site, expr)              \
   do {                                   \
@@ -335,41 +403,39 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
 
   // second MLP matrix: dW2 += g^T dy ; input gradient of the activation
   TRY(stream_order(st, sd, ev[0]));  // dy is complete
-  TRY(gemm(s, SITE_FC2_WGRAD, GEMM_TN, EPI_F32_ACC, a.g, F, dy, h, p.g_w2, h, F, h, T, nullptr, nullptr, 0, nullptr, beta, sd));
+  if (take_w) TRY(wgrad(s, SITE_FC2_WGRAD, layer, WG_FC2, wp, a.g, dy, p.g_w2, F, h, sd));
   if (!s->llama) {
-    TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, dbig, F, T, F, h, nullptr, a.u, F, nullptr, 0, st));  // du
+    TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, du, F, T, F, h, nullptr, a.u, F, nullptr, 0, st));  // du
     TRY(stream_order(st, sd, ev[1]));
-    ON_SIDE(SITE_COLSUM, launch_colsum_partial(dbig, T, F, F, part_b1, sd));
+    ON_SIDE(SITE_COLSUM, launch_colsum_partial(du, T, F, F, part_b1, sd));
     ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_b1, cb, F, p.g_b1, beta, sd));
-    TRY(gemm(s, SITE_FC1_WGRAD, GEMM_TN, EPI_F32_ACC, a.c, h, dbig, F, p.g_w1, F, h, F, T, nullptr, nullptr, 0, nullptr, beta, sd));
-    TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, dbig, F, p.w1, F, dsm, h, T, h, F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
   } else {
     TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_BF16, dy, h, p.w2, h, dsm, F, T, F, h, nullptr, nullptr, 0, nullptr, 0, st));  // dm
-    TIMED(SITE_SWIGLU_BWD, launch_swiglu_bwd(dsm, a.u, dbig, T, F, st));                                                     // d(gate|up)
+    TIMED(SITE_SWIGLU_BWD, launch_swiglu_bwd(dsm, a.u, du, T, F, st));                                                       // d(gate|up)
     TRY(stream_order(st, sd, ev[1]));
-    TRY(gemm(s, SITE_FC1_WGRAD, GEMM_TN, EPI_F32_ACC, a.c, h, dbig, 2 * F, p.g_w1, 2 * F, h, 2 * F, T, nullptr, nullptr, 0, nullptr, beta, sd));
-    TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, dbig, 2 * F, p.w1, 2 * F, dsm, h, T, h, 2 * F, nullptr, nullptr, 0, nullptr, 0, st));  // dc
   }
-  if (sd != st) TRY(hipEventRecord(ev[2], sd));  // the side stream is done with dbig
+  if (take_w) TRY(wgrad(s, SITE_FC1_WGRAD, layer, WG_FC1, wp, a.c, du, p.g_w1, h, Fu, sd));
+  TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, du, Fu, p.w1, Fu, dsm, h, T, h, Fu, nullptr, nullptr, 0, nullptr, 0, st));  // dc
+  if (sd != st) TRY(hipEventRecord(ev[2], sd));  // the side stream is done with du
   // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
   TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part_n2, T, h, st));
   TRY(stream_order(st, sd, ev[3]));
   if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n2, nb, h, p.g_ln2_g, beta, sd));
   else ON_SIDE(SITE_COLSUM, launch_colsum_finish3(part_n2, nb, h, p.g_ln2_g, p.g_ln2_b, p.g_b2, beta, sd));
   // output projection
-  TRY(gemm(s, SITE_WO_WGRAD, GEMM_TN, EPI_F32_ACC, a.o, hl, dmid, h, p.g_wo, h, hl, h, T, nullptr, nullptr, 0, nullptr, beta, sd));
+  if (take_w) TRY(wgrad(s, SITE_WO_WGRAD, layer, WG_WO, wp, a.o, dmid, p.g_wo, hl, h, sd));
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
-  // attention (writes dbig: wait until the first MLP matrix's weight gradient has read it)
-  if (sd != st) TRY(hipStreamWaitEvent(st, ev[2], 0));
-  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dbig, delta, B, S, s->nh, s->d, s->causal, st));
-  if (s->llama) TIMED(SITE_ROPE, launch_rope(dbig, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
+  // attention (where dqkv shares its buffer with du: wait until the first MLP matrix's weight gradient has read it)
+  if (sd != st && dqkv == du) TRY(hipStreamWaitEvent(st, ev[2], 0));
+  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dqkv, delta, B, S, s->nh, s->d, s->causal, st));
+  if (s->llama) TIMED(SITE_ROPE, launch_rope(dqkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
   TRY(stream_order(st, sd, ev[4]));
   if (!s->llama) {
-    ON_SIDE(SITE_COLSUM, launch_colsum_partial(dbig, T, 3 * hl, 3 * hl, part_bqkv, sd));
+    ON_SIDE(SITE_COLSUM, launch_colsum_partial(dqkv, T, 3 * hl, 3 * hl, part_bqkv, sd));
     ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_bqkv, cb, 3 * hl, p.g_bqkv, beta, sd));
   }
-  TRY(gemm(s, SITE_QKV_WGRAD, GEMM_TN, EPI_F32_ACC, a.a, h, dbig, 3 * hl, p.g_wqkv, 3 * hl, h, 3 * hl, T, nullptr, nullptr, 0, nullptr, beta, sd));
-  TRY(gemm(s, SITE_QKV_DGRAD, GEMM_NT, EPI_BF16, dbig, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
+  if (take_w) TRY(wgrad(s, SITE_QKV_WGRAD, layer, WG_QKV, wp, a.a, dqkv, p.g_wqkv, h, 3 * hl, sd));
+  TRY(gemm(s, SITE_QKV_DGRAD, GEMM_NT, EPI_BF16, dqkv, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
   // first norm backward; dx = dx_mid + norm_bwd(da); column sums give d(gain), d(offset), d(bo)
   TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part_n1, T, h, st));
   TRY(stream_order(st, sd, ev[5]));
@@ -418,23 +484,86 @@ hipError_t stage_forward(ah_stage* s, int slot, const void* x, void* y, hipStrea
   return hipSuccess;
 }
 
+// The weight-gradient products of every layer over the micro-batches waiting in pend_slots; frees their slots.
+hipError_t flush_wgrads(ah_stage* s, hipStream_t st) {
+  const int n = (int)s->pend_slots.size();
+  if (n == 0) return hipSuccess;
+  WgradPlan wp = {};
+  wp.nseg = n;
+  wp.beta = s->overwrite_wgrads ? 0 : 1;
+  for (int i = 0; i < n; i++) wp.slots[i] = s->pend_slots[i];
+  const int h = s->h, hl = s->hl, F = s->F, Fu = s->llama ? 2 * F : F;
+  for (int l = s->L - 1; l >= 0; l--) {
+    const LayerPtrs p = layer_ptrs(s, l);
+    TRY(wgrad(s, SITE_FC2_WGRAD, l, WG_FC2, wp, nullptr, nullptr, p.g_w2, F, h, st));
+    TRY(wgrad(s, SITE_FC1_WGRAD, l, WG_FC1, wp, nullptr, nullptr, p.g_w1, h, Fu, st));
+    TRY(wgrad(s, SITE_WO_WGRAD, l, WG_WO, wp, nullptr, nullptr, p.g_wo, hl, h, st));
+    TRY(wgrad(s, SITE_QKV_WGRAD, l, WG_QKV, wp, nullptr, nullptr, p.g_wqkv, h, 3 * hl, st));
+  }
+  for (int i = 0; i < n; i++) s->busy[s->pend_slots[i]] = 0;
+  s->pend_slots.clear();
+  s->overwrite_wgrads = false;
+  return hipSuccess;
+}
+
+// Backward of one micro-batch.  Undeferred, every layer takes its weight gradients at once.  Deferred
+// (group > 1), the micro-batch's output-gradient operands are written into the pending block of its position in
+// the group; the last micro-batch of a group takes the products for the whole group, layer by layer as its own
+// backward passes each layer (so they overlap the rest of backward on the side stream), and frees the group's slots.
 hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipStream_t st, hipEvent_t* ev) {
   const int beta = s->overwrite_grads ? 0 : 1;
   char* wsb = (char*)s->bufs.workspace;
+  const bool deferred = s->group > 1 && !s->force_immediate;
+  const int pos = deferred ? (int)s->pend_slots.size() : 0;
+  const bool closes_group = deferred && pos + 1 == s->group;
+  WgradPlan wp = {};
+  wp.nseg = !deferred ? 0 : closes_group ? s->group : -1;
+  wp.beta = deferred ? (s->overwrite_wgrads ? 0 : 1) : beta;
+  if (closes_group) {
+    for (int i = 0; i < pos; i++) wp.slots[i] = s->pend_slots[i];
+    wp.slots[pos] = slot;
+  }
   const void* cur = dy;
   TRY(ensure_side(s));
   // per-site timing wants one kernel at a time: a trace keeps everything on the caller's stream
   const hipStream_t sd = (s->side_ready && !s->tracing) ? s->side : st;
+  if (deferred) {  // the caller may reuse dy once this call's work has run: keep a copy for the deferred product
+    char* keep;
+    (void)pend_bufs(s, pos, s->L - 1, &keep);
+    TRY(launch_copy(keep, dy, (size_t)s->T * s->h * 2, st));
+    cur = keep;
+  }
   if (ev) TRY(hipEventRecord(ev[s->L], st));
   for (int l = s->L - 1; l >= 0; l--) {
     const ActPtrs a = act_ptrs(s, slot, l);
     if (s->recompute) TRY(layer_forward(s, l, a, nullptr, st));
+    BwdBufs bb = {wsb + s->ws.dmid, wsb + s->ws.dbig, wsb + s->ws.dbig};
     void* out = (l == 0) ? dx : (void*)(wsb + ((l & 1) ? s->ws.d1 : s->ws.d0));
-    TRY(layer_backward(s, l, a, cur, out, beta, st, sd));
+    if (deferred) {
+      bb = pend_bufs(s, pos, l, nullptr);
+      if (l > 0) {
+        char* next_dy;
+        (void)pend_bufs(s, pos, l - 1, &next_dy);
+        out = next_dy;
+      }
+    }
+    TRY(layer_backward(s, l, a, cur, out, beta, bb, wp, st, sd));
     cur = out;
     if (ev) TRY(hipEventRecord(ev[l], st));
   }
   s->overwrite_grads = false;
+  if (!deferred) {
+    s->overwrite_wgrads = false;
+    s->busy[slot] = 0;
+  } else if (closes_group) {
+    for (int i = 0; i < pos; i++) s->busy[s->pend_slots[i]] = 0;
+    s->busy[slot] = 0;
+    s->pend_slots.clear();
+    s->overwrite_wgrads = false;
+  } else {
+    s->pend_slots.push_back(slot);
+    s->busy[slot] = 2;
+  }
   return hipSuccess;
 }
 
@@ -475,6 +604,8 @@ extern "C" int ah_stage_create(const ah_stage_config_t* cfg, const ah_stage_buff
   s->bufs = *bufs;
   s->busy.assign(cfg->max_in_flight, 0);
   s->overwrite_grads = true;
+  s->overwrite_wgrads = true;
+  s->force_immediate = false;
   s->rope_ready = false;
   s->side = nullptr;
   s->side_ready = false;
@@ -512,6 +643,7 @@ extern "C" int ah_stage_forward(ah_stage_t* st, int slot, const void* x, void* y
   discard_stale_hip_error();
   if (!st || !x || !y) return set_error(AH_EINVAL, "ah_stage_forward: NULL argument");
   if (slot < 0 || slot >= (int)st->busy.size()) return set_error(AH_EINVAL, "ah_stage_forward: slot %d out of range [0, %zu)", slot, st->busy.size());
+  if (st->busy[slot] == 2) return set_error(AH_ESTATE, "ah_stage_forward: slot %d holds a micro-batch whose weight gradients are pending (its group is not complete: ah_stage_flush_grads)", slot);
   if (st->busy[slot]) return set_error(AH_ESTATE, "ah_stage_forward: slot %d still holds a micro-batch awaiting backward", slot);
   int rc = hip_status(stage_forward(st, slot, x, y, (hipStream_t)stream, nullptr), "ah_stage_forward");
   if (rc == AH_OK) st->busy[slot] = 1;
@@ -522,10 +654,14 @@ extern "C" int ah_stage_backward(ah_stage_t* st, int slot, const void* dy, void*
   discard_stale_hip_error();
   if (!st || !dy || !dx) return set_error(AH_EINVAL, "ah_stage_backward: NULL argument");
   if (slot < 0 || slot >= (int)st->busy.size()) return set_error(AH_EINVAL, "ah_stage_backward: slot %d out of range [0, %zu)", slot, st->busy.size());
-  if (!st->busy[slot]) return set_error(AH_ESTATE, "ah_stage_backward: slot %d holds no forward pass", slot);
-  int rc = hip_status(stage_backward(st, slot, dy, dx, (hipStream_t)stream, nullptr), "ah_stage_backward");
-  if (rc == AH_OK) st->busy[slot] = 0;
-  return rc;
+  if (st->busy[slot] != 1) return set_error(AH_ESTATE, "ah_stage_backward: slot %d holds no forward pass awaiting backward", slot);
+  return hip_status(stage_backward(st, slot, dy, dx, (hipStream_t)stream, nullptr), "ah_stage_backward");
+}
+
+extern "C" int ah_stage_flush_grads(ah_stage_t* st, void* stream) {
+  discard_stale_hip_error();
+  if (!st) return set_error(AH_EINVAL, "ah_stage_flush_grads: NULL argument");
+  return hip_status(flush_wgrads(st, (hipStream_t)stream), "ah_stage_flush_grads");
 }
 
 extern "C" int ah_stage_grads(ah_stage_t* st, float** dev_ptr, uint64_t* n_elems) {
@@ -537,7 +673,9 @@ extern "C" int ah_stage_grads(ah_stage_t* st, float** dev_ptr, uint64_t* n_elems
 
 extern "C" int ah_stage_zero_grads(ah_stage_t* st, void* /*stream*/) {
   if (!st) return set_error(AH_EINVAL, "ah_stage_zero_grads: NULL argument");
+  if (!st->pend_slots.empty()) return set_error(AH_ESTATE, "ah_stage_zero_grads: %zu micro-batches still wait for their weight gradients (ah_stage_flush_grads first)", st->pend_slots.size());
   st->overwrite_grads = true;
+  st->overwrite_wgrads = true;
   return AH_OK;
 }
 
@@ -569,8 +707,9 @@ extern "C" int ah_stage_profile(ah_stage_t* st, int warmup, int iters, ah_stage_
   void* dx = wsb + st->ws.prof_dx;
   std::vector<std::vector<float>> tf(L), tb(L);
   std::vector<float> sf, sb, ti;
+  st->force_immediate = true;  // a layer's backward time includes its weight gradients
   for (int it = 0; it < warmup + iters && e == hipSuccess; it++) {
-    st->overwrite_grads = true;
+    st->overwrite_grads = st->overwrite_wgrads = true;
     e = stage_forward(st, 0, px, y, s, ef.data());
     if (e == hipSuccess) e = stage_backward(st, 0, pdy, dx, s, eb.data());
     if (e == hipSuccess) e = hipStreamSynchronize(s);
@@ -583,13 +722,18 @@ extern "C" int ah_stage_profile(ah_stage_t* st, int warmup, int iters, ah_stage_
     (void)hipEventElapsedTime(&ms, ef[0], ef[L]); sf.push_back(ms);
     (void)hipEventElapsedTime(&ms, eb[L], eb[0]); sb.push_back(ms);
   }
+  st->force_immediate = false;
+  // the iteration as configured: with deferred weight gradients each micro-batch of a group takes a slot of its own
+  const int nslots = (int)st->busy.size();
   for (int it = 0; it < std::min(warmup, 2) + iters && e == hipSuccess; it++) {
-    st->overwrite_grads = true;
+    st->overwrite_grads = st->overwrite_wgrads = true;
     e = hipEventRecord(it0, s);
     for (int k = 0; k < K && e == hipSuccess; k++) {
-      e = stage_forward(st, 0, px, y, s, nullptr);
-      if (e == hipSuccess) e = stage_backward(st, 0, pdy, dx, s, nullptr);
+      const int slot = st->group > 1 ? k % nslots : 0;
+      e = stage_forward(st, slot, px, y, s, nullptr);
+      if (e == hipSuccess) e = stage_backward(st, slot, pdy, dx, s, nullptr);
     }
+    if (e == hipSuccess) e = flush_wgrads(st, s);
     if (e == hipSuccess) e = hipEventRecord(it1, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     float ms;
@@ -599,7 +743,10 @@ extern "C" int ah_stage_profile(ah_stage_t* st, int warmup, int iters, ah_stage_
   for (auto& v : eb) (void)hipEventDestroy(v);
   (void)hipEventDestroy(it0);
   (void)hipEventDestroy(it1);
-  st->overwrite_grads = true;
+  st->force_immediate = false;
+  st->pend_slots.clear();
+  std::fill(st->busy.begin(), st->busy.end(), 0);
+  st->overwrite_grads = st->overwrite_wgrads = true;
   if (e != hipSuccess) return hip_status(e, "ah_stage_profile");
   for (int l = 0; l < L; l++) { out->fwd_ms[l] = median(tf[l]); out->bwd_ms[l] = median(tb[l]); }
   out->stage_fwd_ms = median(sf);
@@ -626,12 +773,13 @@ extern "C" int ah_stage_trace_end(ah_stage_t* st, ah_trace_entry_t* out, int cap
   hipError_t e = hipDeviceSynchronize();
   if (e != hipSuccess) return hip_status(e, "ah_stage_trace_end");
   double total[SITE_COUNT] = {0};
-  long launches[SITE_COUNT] = {0};
+  long launches[SITE_COUNT] = {0}, mults[SITE_COUNT] = {0};
   for (size_t i = 0; i + 1 < st->ev_used; i += 2) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, st->ev_pool[i], st->ev_pool[i + 1]) != hipSuccess) continue;
     total[st->ev_site[i / 2]] += ms;
     launches[st->ev_site[i / 2]]++;
+    mults[st->ev_site[i / 2]] += st->ev_mult[i / 2];
   }
   st->ev_used = 0;
   // algorithmic work per launch: 2*M*N*K flops for the GEMMs, causal-half flops for masked attention (all S*S pairs without the mask)
@@ -659,7 +807,7 @@ extern "C" int ah_stage_trace_end(ah_stage_t* st, ah_trace_entry_t* out, int cap
     snprintf(o.name, sizeof o.name, "%s", kSiteNames[sidx]);
     o.launches = launches[sidx];
     o.total_ms = total[sidx];
-    o.flops_per_launch = flops[sidx];
+    o.flops_per_launch = flops[sidx] * ((double)mults[sidx] / launches[sidx]);  // deferred weight gradients cover several micro-batches per launch
     o.bytes_per_launch = bytes[sidx];
   }
   *n_out = n;

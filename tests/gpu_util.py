@@ -24,11 +24,12 @@ def rel_l2(got, ref):
     return float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got))
 
 
-def make_cfgs(w, max_in_flight=1, recompute=None):
+def make_cfgs(w, max_in_flight=1, recompute=None, wgrad_group=0):
     nh, hl, Fl = SI.local_dims(w)
     gcfg = P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
                               head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
-                              max_in_flight=max_in_flight, recompute=w["recompute"] if recompute is None else recompute)
+                              max_in_flight=max(max_in_flight, wgrad_group), recompute=w["recompute"] if recompute is None else recompute,
+                              wgrad_group=wgrad_group)
     ocfg = R.StageCfg(w["arch"], w["n_layers"], w["hidden"], nh, w["head_dim"], Fl, w["seq"],
                       1e-6 if w["arch"] == "llama" else 1e-5, 10000.0)
     return gcfg, ocfg
@@ -42,17 +43,26 @@ def load_params(stage, params):
 
 
 def run_gpu(stage, xs, dys):
-    """F0 B0 F1 B1 ... on slot 0; returns ys, dxs (numpy float64) and leaves grads in the stage."""
+    """F0 B0 F1 B1 ... ; returns ys, dxs (numpy float64) and leaves grads in the stage.  Undeferred everything
+    runs on slot 0; with deferred weight gradients a micro-batch keeps its slot until its group is taken, so the
+    slots rotate, the input buffers are overwritten after each call (the library must have kept what it still
+    needs) and an incomplete last group is flushed."""
     stage.zero_grads()
+    group = max(int(stage.cfg.wgrad_group), 1)
     ys, dxs = [], []
-    for x, dy in zip(xs, dys):
+    for m, (x, dy) in enumerate(zip(xs, dys)):
         xd, dyd = to_dev(x), to_dev(dy)
         y, dx = torch.empty_like(xd), torch.empty_like(xd)
-        stage.forward(0, xd, y)
-        stage.backward(0, dyd, dx)
+        slot = m % stage.cfg.max_in_flight if group > 1 else 0
+        stage.forward(slot, xd, y)
+        stage.backward(slot, dyd, dx)
+        xd.zero_()
+        dyd.zero_()
         torch.cuda.synchronize()
         ys.append(to_np(y))
         dxs.append(to_np(dx))
+    stage.flush_grads()
+    torch.cuda.synchronize()
     return ys, dxs
 
 

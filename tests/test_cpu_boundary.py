@@ -102,4 +102,32 @@ def test_gemm_entry_points_refuse_bad_shapes_without_touching_the_device():
     assert lib.ah_gemm_nn(1, 1, None, 1, 100, 128, 128, None) == 5
     assert lib.ah_gemm_nt(None, 1, 1, 128, 128, 128, None) == 1
     assert lib.ah_gemm_tn(1, 1, 1, 128, 128, 128, 2, None) == 1
+    C = ctypes
+    one = (C.c_void_p * 17)(*([1] * 17))
+    assert lib.ah_gemm_tn_segmented(one, one, 17, 1, 128, 128, 128, 0, None) == 5   # too many pieces
+    assert lib.ah_gemm_tn_segmented(one, one, 2, 1, 128, 128, 100, 0, None) == 5    # piece length not a multiple of 128
+    assert lib.ah_gemm_tn_segmented(one, one, 0, 1, 128, 128, 128, 0, None) == 5
+    assert lib.ah_gemm_tn_segmented(None, one, 1, 1, 128, 128, 128, 0, None) == 1
+    hole = (C.c_void_p * 2)(1, None)
+    assert lib.ah_gemm_tn_segmented(hole, one, 2, 1, 128, 128, 128, 0, None) == 1   # a NULL piece
+
     assert lib.ah_attention_fwd(1, 1, 1, 1, 100, 1, 128, 1, None) == 5
+
+
+def test_deferred_weight_gradient_configuration_and_sizes():
+    """wgrad_group: range, its two preconditions, and the workspace it adds (G * layers blocks of the four
+    output-gradient operands), checked against the byte count written out by hand."""
+    base = dict(arch="gpt", n_layers=3, hidden=256, n_heads=4, head_dim=64, ffn=1024, seq=128, mb=2)
+    for bad in (dict(wgrad_group=2, max_in_flight=1), dict(wgrad_group=17, max_in_flight=32), dict(wgrad_group=-1),
+                dict(wgrad_group=2, max_in_flight=2, recompute=1)):
+        with pytest.raises(P.AhError) as e:
+            query_sizes(P.StageConfig.make(**base, **bad))
+        assert e.value.status == 1, bad
+    s0 = query_sizes(P.StageConfig.make(**base, max_in_flight=4))
+    s1 = query_sizes(P.StageConfig.make(**base, max_in_flight=4, wgrad_group=1))
+    s4 = query_sizes(P.StageConfig.make(**base, max_in_flight=4, wgrad_group=4))
+    assert s0 == s1
+    T, h, hl, F = 256, 256, 256, 1024
+    block = 2 * T * (h + h + F + 3 * hl)
+    assert s4["workspace_bytes"] - s0["workspace_bytes"] == 4 * 3 * block
+    assert {k: v for k, v in s4.items() if k != "workspace_bytes"} == {k: v for k, v in s0.items() if k != "workspace_bytes"}

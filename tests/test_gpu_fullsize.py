@@ -148,3 +148,48 @@ def test_benchmark_iteration_properties():
     iteration(restart=False)                                                            # accumulate a second pass on top
     err = ((st.grads.double() - 2 * g1.double()).norm() / (2 * g1.double()).norm()).item()
     assert err <= 1e-6, err
+
+
+def test_benchmark_iteration_with_deferred_weight_gradients():
+    """gpt7b_tp2 as bench.py runs it by default (one weight-gradient product per layer matrix over all 8
+    micro-batches, 32768 tokens on the k axis) against the per-micro-batch accumulation: same y and dx bit for
+    bit, same vector gradients bit for bit, matrices up to fp32 summation order; bit-reproducible; and the
+    profiler's iteration (which rotates the slots itself) runs in this mode."""
+    w = SI.WORKLOADS["gpt7b_tp2"]
+    T, K = w["mb"] * w["seq"], w["n_mb"]
+    torch.manual_seed(2)
+    xs = [torch.randn(T, w["hidden"], device="cuda").to(torch.bfloat16) for _ in range(K)]
+    dys = [torch.randn(T, w["hidden"], device="cuda").to(torch.bfloat16) for _ in range(K)]
+    results = []
+    for G in (1, K):
+        gcfg, _ = U.make_cfgs(w, wgrad_group=G)
+        st = P.Stage(gcfg)
+        torch.manual_seed(3)
+        st.params.normal_(0.0, 0.02)
+        for l in range(w["n_layers"]):
+            st.param_view(l, "ln1_g").fill_(1.0)
+            st.param_view(l, "ln2_g").fill_(1.0)
+        ys, dxs = [torch.empty_like(x) for x in xs], [torch.empty_like(x) for x in xs]
+        for rep in range(2 if G > 1 else 1):
+            st.zero_grads()
+            for m in range(K):
+                st.forward(m % G, xs[m], ys[m])
+                st.backward(m % G, dys[m], dxs[m])
+            st.flush_grads()
+            torch.cuda.synchronize()
+            if rep == 0:
+                first = st.grads.clone()
+        assert torch.equal(first, st.grads)
+        del first
+        results.append((ys, dxs, st))
+    (y0, dx0, s0), (y1, dx1, s1) = results
+    assert all(torch.equal(a, b) for a, b in zip(y0 + dx0, y1 + dx1))
+    for l in range(w["n_layers"]):
+        for name in ("ln1_g", "ln1_b", "bqkv", "bo", "ln2_g", "ln2_b", "b1", "b2"):
+            assert torch.equal(s0.grad_view(l, name), s1.grad_view(l, name)), (l, name)
+        for name in ("wqkv", "wo", "w1", "w2"):
+            a, b = s0.grad_view(l, name).double(), s1.grad_view(l, name).double()
+            err = ((a - b).norm() / a.norm()).item()
+            assert err <= 2e-6, (l, name, err)
+    prof = s1.profile(warmup=1, iters=2)   # overwrites the gradients: last
+    assert prof["iteration_ms"] > 0 and all(t > 0 for t in prof["bwd_ms"])

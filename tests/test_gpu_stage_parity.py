@@ -71,6 +71,86 @@ def test_recompute_is_bit_identical(name):
     assert torch.equal(outs[0][2], outs[1][2])
 
 
+@pytest.mark.parametrize("name,n_mb,group", [("tiny", 4, 2), ("tiny", 5, 3), ("gpt_d128_tp2", 3, 3), ("llama_small", 3, 2),
+                                             ("bert_tiny", 2, 16)])
+def test_deferred_weight_gradients(name, n_mb, group):
+    """Weight-gradient products taken once per group of micro-batches (full groups, an incomplete last group
+    that needs the flush, a group larger than the iteration): against the oracle at the usual gates, and
+    against the undeferred run: y, dx and the vector gradients bit for bit (their path is the same), the
+    matrices up to fp32 summation order."""
+    w = dict(SI.WORKLOADS[name] if name in SI.WORKLOADS else REDUCED[name], n_mb=n_mb)
+    st0, ys0, dxs0 = _run_case(w, n_mb)
+    st1, ys1, dxs1 = _run_case(w, n_mb, wgrad_group=group)
+    assert all(np.array_equal(a, b) for a, b in zip(ys0 + dxs0, ys1 + dxs1))
+    for l in range(w["n_layers"]):
+        for pname in SI.draw_layer_params(w, l):
+            g0, g1 = st0.grad_view(l, pname), st1.grad_view(l, pname)
+            if g0.dim() == 1:
+                assert torch.equal(g0, g1), (l, pname)
+            else:
+                assert U.rel_l2(U.to_np(g1), U.to_np(g0)) <= 2e-6, (l, pname)
+
+
+def test_deferred_weight_gradients_slot_rules():
+    w = SI.WORKLOADS["tiny"]
+    gcfg, _ = U.make_cfgs(w, max_in_flight=3, wgrad_group=3)
+    st = P.Stage(gcfg)
+    x = torch.zeros(w["mb"] * w["seq"], w["hidden"], dtype=torch.bfloat16, device="cuda")
+    y = torch.empty_like(x)
+    st.forward(0, x, y)
+    st.backward(0, x, y)
+    with pytest.raises(P.AhError) as e:      # slot 0 waits for its group
+        st.forward(0, x, y)
+    assert e.value.status == 3
+    with pytest.raises(P.AhError) as e:      # and has had its backward
+        st.backward(0, x, y)
+    assert e.value.status == 3
+    with pytest.raises(P.AhError) as e:
+        st.zero_grads()
+    assert e.value.status == 3
+    st.flush_grads()
+    st.zero_grads()
+    st.forward(0, x, y)                      # free again
+    st.backward(0, x, y)
+    st.forward(1, x, y)
+    st.backward(1, x, y)
+    st.forward(2, x, y)
+    st.backward(2, x, y)                     # closes the group: all three slots free
+    for slot in (0, 1, 2):
+        st.forward(slot, x, y)
+    torch.cuda.synchronize()
+    for bad in (dict(wgrad_group=2, max_in_flight=1), dict(wgrad_group=17, max_in_flight=32), dict(wgrad_group=2, max_in_flight=2, recompute=1)):
+        cfg = P.StageConfig.make(arch="gpt", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=1024, seq=128, mb=2, **bad)
+        with pytest.raises(P.AhError) as e:
+            P.query_sizes(cfg)
+        assert e.value.status == 1
+
+
+@pytest.mark.parametrize("M,N,seg_k,n_seg,beta", [(128, 128, 128, 1, 0), (384, 256, 128, 3, 1), (256, 640, 384, 2, 1), (512, 384, 256, 5, 0),
+                                                  (128, 256, 128, 16, 1)])
+def test_gemm_tn_over_pieces_of_the_k_axis(M, N, seg_k, n_seg, beta):
+    """C = beta C + sum_i A_i^T B_i with the pieces in separate buffers, element by element against float64."""
+    rng = np.random.default_rng(11)
+    As = [SI.round_bf16(rng.standard_normal((seg_k, M), dtype=np.float32)) for _ in range(n_seg)]
+    Bs = [SI.round_bf16(rng.standard_normal((seg_k, N), dtype=np.float32)) for _ in range(n_seg)]
+    C0 = rng.standard_normal((M, N), dtype=np.float32)
+    # the pieces live in unrelated allocations, in shuffled order, with guard rows of NaN around each
+    order = rng.permutation(n_seg)
+    Ad, Bd = [None] * n_seg, [None] * n_seg
+    for i in order:
+        for src, dst, width in ((As, Ad, M), (Bs, Bd, N)):
+            buf = torch.full((seg_k + 16, width), float("nan"), dtype=torch.bfloat16, device="cuda")
+            buf[8:8 + seg_k] = U.to_dev(src[i])
+            dst[i] = buf[8:8 + seg_k]
+    C = torch.from_numpy(C0).cuda()
+    P.gemm_tn_segmented(Ad, Bd, C, beta)
+    torch.cuda.synchronize()
+    ref = beta * C0.astype(np.float64) + sum(a.astype(np.float64).T @ b.astype(np.float64) for a, b in zip(As, Bs))
+    got = C.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= 1e-4 * np.sqrt(seg_k * n_seg) + 1e-5 * np.abs(ref).max()
+
+
 def test_deterministic_and_slot_independent():
     """Same inputs twice -> same bits; an interleaved 1F1B pattern over 3 slots -> same bits."""
     w = SI.WORKLOADS["tiny"]
