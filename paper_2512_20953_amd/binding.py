@@ -146,7 +146,7 @@ class Stage:
         self._h = h
 
     def close(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and lib is not None:   # at interpreter shutdown the module globals may be gone already
             lib.ah_stage_destroy(self._h)
             self._h = None
 

@@ -614,6 +614,12 @@ hipError_t run_tile(int t, const GemmArgs& a, hipStream_t s) {
 
 }  // namespace
 
+int gemm_tile_area(int M, int N, GemmLayout layout) {
+  if (!gemm_shape_ok(M, N, 128)) return 0;
+  const int t = pick_tile(M, N, layout == GEMM_TN);
+  return t < 0 ? 0 : kTiles[t].bm * kTiles[t].bn;
+}
+
 hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in, hipStream_t s) {
   GemmArgs a = a_in;
   static int grp = -1, remap = -1;

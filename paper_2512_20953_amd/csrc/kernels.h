@@ -38,6 +38,7 @@ struct GemmArgs {
 // M, N, K multiples of 128, all leading dimensions multiples of 8.
 hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, hipStream_t s);
 bool gemm_shape_ok(int M, int N, int K);
+int gemm_tile_area(int M, int N, GemmLayout layout);  // rows x columns of the tile launch_gemm would pick for an M x N output
 bool gemm_segments_ok(int seg_k, int n_seg);  // seg_k a positive multiple of 128, 1 <= n_seg <= kMaxGemmSegments
 
 // ---- attention (d = 64 or 128, S multiple of 128) ----

@@ -55,6 +55,7 @@ struct ah_stage {
   // Deferred weight gradients: with group > 1 the four weight-gradient products of a layer run once per `group`
   // micro-batches, over the concatenation of their tokens, instead of once per micro-batch.
   int group;
+  bool defer_matrix[4];         // by WgradWhich: small outputs stay undeferred (see plan())
   bool force_immediate;         // the profiler's per-layer timing runs undeferred
   PendLayout pend;
   std::vector<int> pend_slots;  // slots of the micro-batches waiting, in backward order
@@ -113,6 +114,18 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
   s->causal = c->arch != AH_ARCH_BERT;
   s->recompute = c->recompute != 0;
   s->group = c->wgrad_group > 1 ? c->wgrad_group : 1;
+  {
+    // A deferred product runs at the end of its group with a k axis G times as long.  That pays for the outputs
+    // large enough for the 256-wide tiles (fewer fp32 passes over a large matrix, one prologue and epilogue).  A
+    // small output, which gets 128 x 128 tiles that use a CU poorly on their own, is better taken per micro-batch:
+    // the side stream runs it beside the rest of backward, and its read-modify-write is small anyway (measured on
+    // the BERT-Large stage, whose matrices are all of that kind: 26.7 ms per step undeferred, 29.1 deferred).
+    const char* e = getenv("AH_DEFER_MIN_TILE_AREA");  // tuning aid
+    const int min_area = e ? atoi(e) : 256 * 128;
+    const int Fu_ = (c->arch == AH_ARCH_LLAMA ? 2 : 1) * s->F;
+    const int mn[4][2] = {{s->F, s->h}, {s->h, Fu_}, {s->hl, s->h}, {s->h, 3 * s->hl}};  // WG_FC2, WG_FC1, WG_WO, WG_QKV
+    for (int i = 0; i < 4; i++) s->defer_matrix[i] = gemm_tile_area(mn[i][0], mn[i][1], GEMM_TN) >= min_area;
+  }
   s->eps = c->norm_eps > 0 ? c->norm_eps : (s->llama ? 1e-6f : 1e-5f);
   s->rope_base = c->rope_base > 0 ? c->rope_base : 10000.f;
   const int h = s->h, hl = s->hl, F = s->F;
@@ -321,17 +334,21 @@ BwdBufs pend_bufs(const ah_stage* s, int pos, int layer, char** dy_out) {
 //   nseg <  0: leaves them to a later call;
 //   nseg >  0: takes them over the nseg micro-batches in slots[] (group positions 0 .. nseg - 1), whose token
 //              axes are concatenated inside the product.
-struct WgradPlan { int nseg; int slots[kMaxGemmSegments]; int beta; };
+// Matrices that are never deferred (defer_matrix) are taken now whatever nseg says, with beta_now.
+struct WgradPlan { int nseg; int slots[kMaxGemmSegments]; int beta, beta_now; };
 
 enum WgradWhich { WG_FC2, WG_FC1, WG_WO, WG_QKV };
 
 // One weight-gradient product C[M, N] (+)= sum over the plan's micro-batches of act^T dY.
 hipError_t wgrad(ah_stage* s, int site, int layer, WgradWhich which, const WgradPlan& wp, const void* act, const void* dY, float* C,
                  int M, int N, hipStream_t st) {
+  const bool now = wp.nseg == 0 || !s->defer_matrix[which];
+  if (now && !act) return hipSuccess;  // a flush: this matrix was taken with each micro-batch
+  if (!now && wp.nseg < 0) return hipSuccess;
   GemmArgs g = {};
   g.A = act; g.B = dY; g.C = C;
-  g.lda = M; g.ldb = N; g.ldc = N; g.M = M; g.N = N; g.K = s->T; g.beta = wp.beta;
-  if (wp.nseg > 0) {
+  g.lda = M; g.ldb = N; g.ldc = N; g.M = M; g.N = N; g.K = s->T; g.beta = now ? wp.beta_now : wp.beta;
+  if (!now) {
     g.seg_k = s->T; g.n_seg = wp.nseg; g.K = s->T * wp.nseg;
     for (int i = 0; i < wp.nseg; i++) {
       const ActPtrs a = act_ptrs(s, wp.slots[i], layer);
@@ -341,7 +358,7 @@ hipError_t wgrad(ah_stage* s, int site, int layer, WgradWhich which, const Wgrad
       g.segB[i] = which == WG_FC2 ? dy : which == WG_FC1 ? b.du : which == WG_WO ? b.dmid : b.dqkv;
     }
   }
-  SiteTimer t(s, site, st, wp.nseg > 0 ? wp.nseg : 1);
+  SiteTimer t(s, site, st, now ? 1 : wp.nseg);
   return launch_gemm(GEMM_TN, EPI_F32_ACC, g, st);
 }
 
@@ -391,7 +408,6 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   float* delta = (float*)(wsb + s->ws.delta);
   const int nb = norm_bwd_blocks(T), cb = colsum_blocks(T);
   const bool rms = s->llama;
-  const bool take_w = wp.nseg >= 0;
   hipEvent_t* ev = s->sync_ev;
 #define ON_SIDE(site, expr)              \
   do {                                   \
@@ -403,7 +419,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
 
   // second MLP matrix: dW2 += g^T dy ; input gradient of the activation
   TRY(stream_order(st, sd, ev[0]));  // dy is complete
-  if (take_w) TRY(wgrad(s, SITE_FC2_WGRAD, layer, WG_FC2, wp, a.g, dy, p.g_w2, F, h, sd));
+  TRY(wgrad(s, SITE_FC2_WGRAD, layer, WG_FC2, wp, a.g, dy, p.g_w2, F, h, sd));
   if (!s->llama) {
     TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, du, F, T, F, h, nullptr, a.u, F, nullptr, 0, st));  // du
     TRY(stream_order(st, sd, ev[1]));
@@ -414,7 +430,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
     TIMED(SITE_SWIGLU_BWD, launch_swiglu_bwd(dsm, a.u, du, T, F, st));                                                       // d(gate|up)
     TRY(stream_order(st, sd, ev[1]));
   }
-  if (take_w) TRY(wgrad(s, SITE_FC1_WGRAD, layer, WG_FC1, wp, a.c, du, p.g_w1, h, Fu, sd));
+  TRY(wgrad(s, SITE_FC1_WGRAD, layer, WG_FC1, wp, a.c, du, p.g_w1, h, Fu, sd));
   TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, du, Fu, p.w1, Fu, dsm, h, T, h, Fu, nullptr, nullptr, 0, nullptr, 0, st));  // dc
   if (sd != st) TRY(hipEventRecord(ev[2], sd));  // the side stream is done with du
   // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
@@ -423,7 +439,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n2, nb, h, p.g_ln2_g, beta, sd));
   else ON_SIDE(SITE_COLSUM, launch_colsum_finish3(part_n2, nb, h, p.g_ln2_g, p.g_ln2_b, p.g_b2, beta, sd));
   // output projection
-  if (take_w) TRY(wgrad(s, SITE_WO_WGRAD, layer, WG_WO, wp, a.o, dmid, p.g_wo, hl, h, sd));
+  TRY(wgrad(s, SITE_WO_WGRAD, layer, WG_WO, wp, a.o, dmid, p.g_wo, hl, h, sd));
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
   // attention (where dqkv shares its buffer with du: wait until the first MLP matrix's weight gradient has read it)
   if (sd != st && dqkv == du) TRY(hipStreamWaitEvent(st, ev[2], 0));
@@ -434,7 +450,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
     ON_SIDE(SITE_COLSUM, launch_colsum_partial(dqkv, T, 3 * hl, 3 * hl, part_bqkv, sd));
     ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_bqkv, cb, 3 * hl, p.g_bqkv, beta, sd));
   }
-  if (take_w) TRY(wgrad(s, SITE_QKV_WGRAD, layer, WG_QKV, wp, a.a, dqkv, p.g_wqkv, h, 3 * hl, sd));
+  TRY(wgrad(s, SITE_QKV_WGRAD, layer, WG_QKV, wp, a.a, dqkv, p.g_wqkv, h, 3 * hl, sd));
   TRY(gemm(s, SITE_QKV_DGRAD, GEMM_NT, EPI_BF16, dqkv, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
   // first norm backward; dx = dx_mid + norm_bwd(da); column sums give d(gain), d(offset), d(bo)
   TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part_n1, T, h, st));
@@ -519,6 +535,7 @@ hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipSt
   WgradPlan wp = {};
   wp.nseg = !deferred ? 0 : closes_group ? s->group : -1;
   wp.beta = deferred ? (s->overwrite_wgrads ? 0 : 1) : beta;
+  wp.beta_now = beta;
   if (closes_group) {
     for (int i = 0; i < pos; i++) wp.slots[i] = s->pend_slots[i];
     wp.slots[pos] = slot;
