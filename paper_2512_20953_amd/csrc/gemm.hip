@@ -16,6 +16,8 @@
 #include "common.h"
 #include "kernels.h"
 #include <cstdlib>
+#include <mutex>
+#include <vector>
 
 namespace ah {
 
@@ -576,23 +578,70 @@ const TileCfg kTiles[] = {{256, 256, 2, 2, 1.00f, 1.00f}, {256, 128, 2, 2, 1.35f
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int kAutoTiles = 4;  // the automatic choice looks at the first kAutoTiles entries
 
-int pick_tile(int M, int N, bool tn) {
+int forced_tile() {
   static int forced = -2;
   if (forced == -2) {
     const char* e = getenv("AH_GEMM_TILE");  // tuning aid: index into kTiles
     forced = e ? atoi(e) : -1;
   }
+  return forced;
+}
+
+// cost of covering an M x n output with tile i, in units of (tile area x relative cost) per round
+float tile_cost(int i, int M, int n, bool tn) {
+  const long tiles = (long)(M / kTiles[i].bm) * (n / kTiles[i].bn);
+  const long rounds = (tiles + 255) / 256;
+  return rounds * (tn ? kTiles[i].cost_tn : kTiles[i].cost) * kTiles[i].bm * kTiles[i].bn;
+}
+
+int pick_tile(int M, int N, bool tn) {
+  const int forced = forced_tile();
   if (forced >= 0 && forced < kNumTiles && M % kTiles[forced].bm == 0 && N % kTiles[forced].bn == 0) return forced;
   int best = -1;
   float best_t = 0;
   for (int i = 0; i < kAutoTiles; i++) {
     if (M % kTiles[i].bm || N % kTiles[i].bn) continue;
-    long tiles = (long)(M / kTiles[i].bm) * (N / kTiles[i].bn);
-    long rounds = (tiles + 255) / 256;
-    float t = rounds * (tn ? kTiles[i].cost_tn : kTiles[i].cost) * kTiles[i].bm * kTiles[i].bn;
+    const float t = tile_cost(i, M, N, tn);
     if (best < 0 || t < best_t) { best = i; best_t = t; }
   }
   return best;
+}
+
+// How a launch covers its output: with one tile shape, or as two launches over the column ranges [0, n0) and
+// [n0, N), each with its own tile shape.  The second form is for outputs whose tile count is not a good multiple
+// of the 256 CUs: 4096 x 6144 is 384 tiles of 256 x 256, i.e. two rounds of which the second is half empty (2.0
+// units), or 768 tiles of 256 x 128 in three rounds (2.0 .. 1.9); 256 tiles of 256 x 256 over the first 4096
+// columns and then 256 tiles of 256 x 128 over the rest is two full rounds of 1.0 + 0.63 .. 0.68 units.
+struct Plan { int parts; int tile[2]; int n0; };
+constexpr float kSplitCost = 0.15f * 256 * 256;  // the second launch's gap, prologue and epilogue, in the same units
+
+Plan make_plan(int M, int N, bool tn) {
+  Plan p = {1, {pick_tile(M, N, tn), -1}, N};
+  if (p.tile[0] < 0 || forced_tile() >= 0 || getenv("AH_GEMM_NOSPLIT")) return p;
+  float best = tile_cost(p.tile[0], M, N, tn);
+  for (int n0 = 128; n0 < N; n0 += 128)
+    for (int i = 0; i < kAutoTiles; i++) {
+      if (M % kTiles[i].bm || n0 % kTiles[i].bn) continue;
+      for (int j = 0; j < kAutoTiles; j++) {
+        if (j == i || M % kTiles[j].bm || (N - n0) % kTiles[j].bn) continue;
+        const float t = tile_cost(i, M, n0, tn) + tile_cost(j, M, N - n0, tn) + kSplitCost;
+        if (t < best) { best = t; p = {2, {i, j}, n0}; }
+      }
+    }
+  return p;
+}
+
+// make_plan is a search over a few thousand candidates: remembered per (M, N, layout class)
+Plan cached_plan(int M, int N, bool tn) {
+  struct Entry { int M, N; bool tn; Plan p; };
+  static std::mutex mu;
+  static std::vector<Entry> cache;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const Entry& e : cache)
+    if (e.M == M && e.N == N && e.tn == tn) return e.p;
+  const Plan p = make_plan(M, N, tn);
+  if (cache.size() < 4096) cache.push_back({M, N, tn, p});
+  return p;
 }
 
 template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS, int EPI>
@@ -616,9 +665,45 @@ hipError_t run_tile(int t, const GemmArgs& a, hipStream_t s) {
 
 int gemm_tile_area(int M, int N, GemmLayout layout) {
   if (!gemm_shape_ok(M, N, 128)) return 0;
-  const int t = pick_tile(M, N, layout == GEMM_TN);
-  return t < 0 ? 0 : kTiles[t].bm * kTiles[t].bn;
+  const Plan p = cached_plan(M, N, layout == GEMM_TN);
+  return p.tile[0] < 0 ? 0 : kTiles[p.tile[0]].bm * kTiles[p.tile[0]].bn;
 }
+
+namespace {
+
+hipError_t dispatch(GemmLayout layout, GemmEpilogue epi, int t, const GemmArgs& a, hipStream_t s) {
+  if (layout == GEMM_NN) {
+    if (epi == EPI_BF16) return run_tile<false, true, EPI_BF16>(t, a, s);
+    if (epi == EPI_GELU) return run_tile<false, true, EPI_GELU>(t, a, s);
+    if (epi == EPI_RESID) return run_tile<false, true, EPI_RESID>(t, a, s);
+  } else if (layout == GEMM_NT) {
+    if (epi == EPI_BF16) return run_tile<false, false, EPI_BF16>(t, a, s);
+    if (epi == EPI_GELU_BWD) return run_tile<false, false, EPI_GELU_BWD>(t, a, s);
+  } else if (layout == GEMM_TN) {
+    if (epi == EPI_F32_ACC) return a.beta ? run_tile<true, true, EPI_F32_ACC>(t, a, s) : run_tile<true, true, EPI_F32_SET>(t, a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+// the same problem restricted to output columns [c0, c0 + n)
+GemmArgs column_range(GemmLayout layout, const GemmArgs& a, int c0, int n) {
+  GemmArgs b = a;
+  b.N = n;
+  const bool f32 = layout == GEMM_TN;
+  b.C = f32 ? (void*)((float*)a.C + c0) : (void*)((bf16*)a.C + c0);
+  if (a.C2) b.C2 = (bf16*)a.C2 + c0;
+  if (a.bias) b.bias = (const bf16*)a.bias + c0;
+  if (a.aux) b.aux = (const bf16*)a.aux + c0;
+  if (layout == GEMM_NT) {
+    b.B = (const bf16*)a.B + (size_t)c0 * a.ldb;  // B is [N, K]
+  } else {
+    b.B = (const bf16*)a.B + c0;                  // B is [K, N]
+    for (int i = 0; i < a.n_seg; i++) b.segB[i] = (const bf16*)a.segB[i] + c0;
+  }
+  return b;
+}
+
+}  // namespace
 
 hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in, hipStream_t s) {
   GemmArgs a = a_in;
@@ -633,19 +718,12 @@ hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in
     a.A = a.segA[0];
     a.B = a.segB[0];
   }
-  const int t = pick_tile(a.M, a.N, layout == GEMM_TN);
-  if (t < 0) return hipErrorInvalidValue;
-  if (layout == GEMM_NN) {
-    if (epi == EPI_BF16) return run_tile<false, true, EPI_BF16>(t, a, s);
-    if (epi == EPI_GELU) return run_tile<false, true, EPI_GELU>(t, a, s);
-    if (epi == EPI_RESID) return run_tile<false, true, EPI_RESID>(t, a, s);
-  } else if (layout == GEMM_NT) {
-    if (epi == EPI_BF16) return run_tile<false, false, EPI_BF16>(t, a, s);
-    if (epi == EPI_GELU_BWD) return run_tile<false, false, EPI_GELU_BWD>(t, a, s);
-  } else if (layout == GEMM_TN) {
-    if (epi == EPI_F32_ACC) return a.beta ? run_tile<true, true, EPI_F32_ACC>(t, a, s) : run_tile<true, true, EPI_F32_SET>(t, a, s);
-  }
-  return hipErrorInvalidValue;
+  const Plan p = cached_plan(a.M, a.N, layout == GEMM_TN);
+  if (p.tile[0] < 0) return hipErrorInvalidValue;
+  if (p.parts == 1) return dispatch(layout, epi, p.tile[0], a, s);
+  hipError_t e = dispatch(layout, epi, p.tile[0], column_range(layout, a, 0, p.n0), s);
+  if (e != hipSuccess) return e;
+  return dispatch(layout, epi, p.tile[1], column_range(layout, a, p.n0, a.N - p.n0), s);
 }
 
 }  // namespace ah

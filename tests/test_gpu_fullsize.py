@@ -24,11 +24,12 @@ def _bf16_normal(rng, shape, std):
 
 @pytest.mark.parametrize("layout,M,N,K", [
     ("nn", 4096, 8192, 4096),   # first MLP matrix forward
-    ("nn", 4096, 6144, 4096),   # QKV forward (256x128 tiles)
+    ("nn", 4096, 6144, 4096),   # QKV forward: two launches over column ranges with different tiles
     ("nt", 4096, 2048, 4096),   # out-projection input gradient (256x128 tiles)
     ("nt", 4096, 4096, 8192),   # first MLP matrix input gradient
     ("tn", 8192, 4096, 4096),   # second MLP matrix weight gradient
     ("tn", 2048, 4096, 4096),   # out-projection weight gradient
+    ("tn", 4096, 6144, 4096),   # QKV weight gradient: covered by two launches (256x128 tiles over 2048 columns, 256x256 over 4096)
 ])
 def test_gemm_at_benchmark_shapes_sampled_entries(layout, M, N, K):
     rng = np.random.default_rng(7)
