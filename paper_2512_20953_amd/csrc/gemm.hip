@@ -311,7 +311,7 @@ __device__ __forceinline__ void ring_step(const char* gA, const char* gB, const 
 template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
-  constexpr bool K32 = AKS && BKS;                      // which pipeline
+  constexpr bool K32 = AKS && BKS;  // which pipeline
   constexpr int BUF = (BM > BN ? BM : BN) * 128;        // k64: one ring buffer holds an A or a B tile
   constexpr int RING = K32 ? k32::NS * (BM + BN) * 64 : k64::NB * BUF;
   // the epilogue reuses the ring as staging space
@@ -367,50 +367,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     for (int i = 0; i < BN / 16 / NW; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
     // nk is a multiple of 4 (K is a multiple of 128).  Stage t lives in ring slot t % 4.
     const int nk = g.K / BK, last = nk - 1;
-    // The k axis may be cut into pieces that live in different buffers (kernels.h).  (pA, pB) is the stage to be
-    // fetched next; it walks through a piece by stepA / stepB and jumps to the next piece's base at its end.
-    // Past the last stage it stays put: the last stage is fetched again into a dead slot, which keeps the
-    // in-flight load count uniform.  All of this is wave-uniform scalar arithmetic.
-    const int seg_stages = g.n_seg > 0 ? g.seg_k / BK : nk;
-    const char *pA = gA, *pB = gB;
-    int q = 0, within = 0, seg = 0;
-    auto advance = [&]() {
-      if (q >= last) return;
-      q++;
-      if (++within == seg_stages) {
-        within = 0;
-        seg++;
-        pA = (const char*)((const bf16*)g.segA[seg] + m0);
-        pB = (const char*)((const bf16*)g.segB[seg] + n0);
-      } else {
-        pA += stepA;
-        pB += stepB;
-      }
-    };
-    issue_tile_loads<BM, NW>(pA, offA, sA0, wave);
-    issue_tile_loads<BN, NW>(pB, offB, sB0, wave);
-    advance();
-    issue_tile_loads<BM, NW>(pA, offA, sA1, wave);
-    issue_tile_loads<BN, NW>(pB, offB, sB1, wave);
-    advance();
-    issue_tile_loads<BM, NW>(pA, offA, sA2, wave);
-    issue_tile_loads<BN, NW>(pB, offB, sB2, wave);
-    advance();
+    // The k axis may be cut into pieces that live in different buffers (kernels.h): the outer loop runs over the
+    // pieces, the inner one over the stages of a piece (a multiple of 4).  The stage fetched during local step t
+    // is local stage t + 3; past the end of the piece that is a stage of the next piece, past the end of the last
+    // piece the last stage again (fetched into a dead slot, which keeps the in-flight load count uniform).  The
+    // choice is a scalar select, so the inner loop stays one basic block.
+    const int nseg = g.n_seg > 0 ? g.n_seg : 1;
+    const int seg_stages = nk / nseg;
+    issue_tile_loads<BM, NW>(gA, offA, sA0, wave);
+    issue_tile_loads<BN, NW>(gB, offB, sB0, wave);
+    issue_tile_loads<BM, NW>(gA + stepA, offA, sA1, wave);
+    issue_tile_loads<BN, NW>(gB + stepB, offB, sB1, wave);
+    issue_tile_loads<BM, NW>(gA + 2 * stepA, offA, sA2, wave);
+    issue_tile_loads<BN, NW>(gB + 2 * stepB, offB, sB2, wave);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
     __builtin_amdgcn_s_barrier();
 
     Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
     f0.load(sA0, sB0, 0, wm, wn, lane);
-    // the stage loaded during step t is min(t + 3, last)
-    for (int t = 0; t < nk; t += 4) {
-      ring_step<BM, BN, WGM, WGN, AKS, BKS>(pA, pB, offA, offB, sA3, sB3, sA0, sB0, sA1, sB1, f0, f1, acc, wave, wm, wn, lane);
-      advance();
-      ring_step<BM, BN, WGM, WGN, AKS, BKS>(pA, pB, offA, offB, sA0, sB0, sA1, sB1, sA2, sB2, f0, f1, acc, wave, wm, wn, lane);
-      advance();
-      ring_step<BM, BN, WGM, WGN, AKS, BKS>(pA, pB, offA, offB, sA1, sB1, sA2, sB2, sA3, sB3, f0, f1, acc, wave, wm, wn, lane);
-      advance();
-      ring_step<BM, BN, WGM, WGN, AKS, BKS>(pA, pB, offA, offB, sA2, sB2, sA3, sB3, sA0, sB0, f0, f1, acc, wave, wm, wn, lane);
-      advance();
+    const char *curA = gA, *curB = gB;
+    for (int sg = 0; sg < nseg; sg++) {
+      const bool last_piece = sg + 1 == nseg;
+      const char* nxtA = last_piece ? curA : (const char*)((const bf16*)g.segA[sg + 1] + m0);
+      const char* nxtB = last_piece ? curB : (const char*)((const bf16*)g.segB[sg + 1] + n0);
+      const int lim = last_piece ? seg_stages - 1 : seg_stages + 2;
+#define AH_STAGE_PTRS(u)                                                                                              \
+  (min((u), lim) >= seg_stages ? nxtA + (size_t)(min((u), lim) - seg_stages) * stepA : curA + (size_t)min((u), lim) * stepA), \
+      (min((u), lim) >= seg_stages ? nxtB + (size_t)(min((u), lim) - seg_stages) * stepB : curB + (size_t)min((u), lim) * stepB)
+      for (int t = 0; t < seg_stages; t += 4) {
+        ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 3), offA, offB, sA3, sB3, sA0, sB0, sA1, sB1, f0, f1, acc, wave, wm, wn, lane);
+        ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 4), offA, offB, sA0, sB0, sA1, sB1, sA2, sB2, f0, f1, acc, wave, wm, wn, lane);
+        ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 5), offA, offB, sA1, sB1, sA2, sB2, sA3, sB3, f0, f1, acc, wave, wm, wn, lane);
+        ring_step<BM, BN, WGM, WGN, AKS, BKS>(AH_STAGE_PTRS(t + 6), offA, offB, sA2, sB2, sA3, sB3, sA0, sB0, f0, f1, acc, wave, wm, wn, lane);
+      }
+#undef AH_STAGE_PTRS
+      curA = nxtA;
+      curB = nxtB;
     }
   } else {
     using namespace k64;
@@ -435,6 +427,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     const uint32_t* offF = BF ? offB : offA;
     const uint32_t* offS = BF ? offA : offB;
     const int np = g.K / BK, lastp = np - 1;
+    // In the weight-gradient layout the k axis may be cut into pieces that live in different buffers (kernels.h):
+    // the outer loop runs over the pieces (one piece for the other layouts), the inner one over the k-blocks of a
+    // piece (an even number).  During local k-block j the tiles S_{j+1} and F_{j+2} are fetched; past the end of
+    // the piece those belong to the next piece, past the end of the last piece the last k-block is fetched again.
+    constexpr bool PIECES = AKS && BKS;
+    const int nseg = (PIECES && g.n_seg > 0) ? g.n_seg : 1;
+    const int seg_blocks = np / nseg;
     issue_tile_loads<WF, NW>(gF, offF, ring, wave);                                            // F_0 -> buffer 0
     issue_tile_loads<WS, NW>(gS, offS, ring + BUF, wave);                                      // S_0 -> buffer 1
     issue_tile_loads<WF, NW>(gF + (size_t)min(1, lastp) * stepF, offF, ring + 2 * BUF, wave);  // F_1 -> buffer 2
@@ -444,20 +443,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
     f0.load(ring + (BF ? BUF : 0), ring + (BF ? 0 : BUF), 0, wm, wn, lane);
     int jf = 0, js = 1;  // buffers of F_j and S_j
-    for (int j = 0; j < np; j++) {
-      const int nf = jf + 2 >= NB ? jf + 2 - NB : jf + 2;  // F_{j+1}
-      const int ns = js + 2 >= NB ? js + 2 - NB : js + 2;  // S_{j+1}: loaded now, into the buffer of F_{j-1}
-      const int ff = jf + 4 >= NB ? jf + 4 - NB : jf + 4;  // F_{j+2}: into the buffer of S_{j-1}
-      const char* cA = ring + (BF ? js : jf) * BUF;
-      const char* cB = ring + (BF ? jf : js) * BUF;
-      const char* nA = ring + (BF ? ns : nf) * BUF;
-      const char* nB = ring + (BF ? nf : ns) * BUF;
-      half_even<BM, BN, WGM, WGN, AKS, BKS>(gS + (size_t)min(j + 1, lastp) * stepS, offS, ring + ns * BUF, cA, cB, f0, f1, acc, wave, wm, wn,
-                                            lane);
-      half_odd<BM, BN, WGM, WGN, AKS, BKS>(gF + (size_t)min(j + 2, lastp) * stepF, offF, ring + ff * BUF, cA, cB, nA, nB, f0, f1, acc, wave,
-                                           wm, wn, lane);
-      jf = nf;
-      js = ns;
+    const char *curF = gF, *curS = gS;
+    for (int sg = 0; sg < nseg; sg++) {
+      const bool last_piece = sg + 1 == nseg;
+      const char *nxtF = curF, *nxtS = curS;
+      if constexpr (PIECES) {
+        if (!last_piece) {
+          nxtF = (const char*)((const bf16*)(BF ? g.segB[sg + 1] : g.segA[sg + 1]) + (BF ? n0 : m0));
+          nxtS = (const char*)((const bf16*)(BF ? g.segA[sg + 1] : g.segB[sg + 1]) + (BF ? m0 : n0));
+        }
+      }
+      const int lim = last_piece ? seg_blocks - 1 : seg_blocks + 1;
+      for (int j = 0; j < seg_blocks; j++) {
+        const int nf = jf + 2 >= NB ? jf + 2 - NB : jf + 2;  // F_{j+1}
+        const int ns = js + 2 >= NB ? js + 2 - NB : js + 2;  // S_{j+1}: loaded now, into the buffer of F_{j-1}
+        const int ff = jf + 4 >= NB ? jf + 4 - NB : jf + 4;  // F_{j+2}: into the buffer of S_{j-1}
+        const char* cA = ring + (BF ? js : jf) * BUF;
+        const char* cB = ring + (BF ? jf : js) * BUF;
+        const char* nA = ring + (BF ? ns : nf) * BUF;
+        const char* nB = ring + (BF ? nf : ns) * BUF;
+        const int us = min(j + 1, lim), uf = min(j + 2, lim);
+        const char* pS = (PIECES && us >= seg_blocks) ? nxtS + (size_t)(us - seg_blocks) * stepS : curS + (size_t)us * stepS;
+        const char* pF = (PIECES && uf >= seg_blocks) ? nxtF + (size_t)(uf - seg_blocks) * stepF : curF + (size_t)uf * stepF;
+        half_even<BM, BN, WGM, WGN, AKS, BKS>(pS, offS, ring + ns * BUF, cA, cB, f0, f1, acc, wave, wm, wn, lane);
+        half_odd<BM, BN, WGM, WGN, AKS, BKS>(pF, offF, ring + ff * BUF, cA, cB, nA, nB, f0, f1, acc, wave, wm, wn, lane);
+        jf = nf;
+        js = ns;
+      }
+      curF = nxtF;
+      curS = nxtS;
     }
   }
   __builtin_amdgcn_s_waitcnt(0);  // drain the redundant tail loads before the block's LDS is released
