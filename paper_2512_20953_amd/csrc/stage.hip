@@ -64,8 +64,8 @@ struct ah_stage {
   bool tracing;
   // Second stream for the work of backward that nothing downstream waits for (weight gradients, column-sum
   // reductions); created on first use, joined back into the caller's stream before every return.
-  hipStream_t side;
-  hipEvent_t sync_ev[8];
+  hipStream_t side, side2;  // side2: the dQ kernel of attention backward, beside the dK/dV kernel
+  hipEvent_t sync_ev[10];
   bool side_ready, side_off;
   std::vector<hipEvent_t> ev_pool;           // pairs, in launch order
   std::vector<int> ev_site;                  // site of pair i
@@ -443,7 +443,8 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
   // attention (where dqkv shares its buffer with du: wait until the first MLP matrix's weight gradient has read it)
   if (sd != st && dqkv == du) TRY(hipStreamWaitEvent(st, ev[2], 0));
-  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dqkv, delta, B, S, s->nh, s->d, s->causal, st));
+  const AttnBwdFork fk = {s->side2, ev[7], ev[8]};
+  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dqkv, delta, B, S, s->nh, s->d, s->causal, st, (sd != st && !getenv("AH_NO_ATTN_FORK")) ? &fk : nullptr));
   if (s->llama) TIMED(SITE_ROPE, launch_rope(dqkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
   TRY(stream_order(st, sd, ev[4]));
   if (!s->llama) {
@@ -468,6 +469,8 @@ hipError_t ensure_side(ah_stage* s) {
   if (s->side_ready || s->side_off) return hipSuccess;
   if (getenv("AH_NO_SIDE_STREAM")) { s->side_off = true; return hipSuccess; }
   hipError_t e = hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking);
+  if (e != hipSuccess) return e;
+  e = hipStreamCreateWithFlags(&s->side2, hipStreamNonBlocking);
   if (e != hipSuccess) return e;
   for (auto& v : s->sync_ev) {
     e = hipEventCreateWithFlags(&v, hipEventDisableTiming);
@@ -625,6 +628,7 @@ extern "C" int ah_stage_create(const ah_stage_config_t* cfg, const ah_stage_buff
   s->force_immediate = false;
   s->rope_ready = false;
   s->side = nullptr;
+  s->side2 = nullptr;
   s->side_ready = false;
   s->side_off = false;
   s->tracing = false;
@@ -638,6 +642,8 @@ extern "C" int ah_stage_destroy(ah_stage_t* st) {
     for (hipEvent_t e : st->ev_pool) (void)hipEventDestroy(e);
     if (st->side_ready) {
       (void)hipStreamSynchronize(st->side);
+      (void)hipStreamSynchronize(st->side2);
+      (void)hipStreamDestroy(st->side2);
       for (hipEvent_t e : st->sync_ev) (void)hipEventDestroy(e);
       (void)hipStreamDestroy(st->side);
     }
