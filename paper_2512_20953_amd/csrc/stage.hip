@@ -340,8 +340,12 @@ struct WgradPlan { int nseg; int slots[kMaxGemmSegments]; int beta, beta_now; };
 enum WgradWhich { WG_FC2, WG_FC1, WG_WO, WG_QKV };
 
 // One weight-gradient product C[M, N] (+)= sum over the plan's micro-batches of act^T dY.
+// A product over one micro-batch goes to `sd` (the side stream: beside the rest of backward it hides its tail and
+// the launch gaps); a product over a whole group goes to `st`: it fills the chip for milliseconds, and next to it the
+// kernels of the main chain only slow down (gpt7b_tp2, G = 8: 76.1 ms per step this way, 77.9 with the group's
+// products on the side stream).
 hipError_t wgrad(ah_stage* s, int site, int layer, WgradWhich which, const WgradPlan& wp, const void* act, const void* dY, float* C,
-                 int M, int N, hipStream_t st) {
+                 int M, int N, hipStream_t st, hipStream_t sd) {
   const bool now = wp.nseg == 0 || !s->defer_matrix[which];
   if (now && !act) return hipSuccess;  // a flush: this matrix was taken with each micro-batch
   if (!now && wp.nseg < 0) return hipSuccess;
@@ -358,8 +362,9 @@ hipError_t wgrad(ah_stage* s, int site, int layer, WgradWhich which, const Wgrad
       g.segB[i] = which == WG_FC2 ? dy : which == WG_FC1 ? b.du : which == WG_WO ? b.dmid : b.dqkv;
     }
   }
-  SiteTimer t(s, site, st, now ? 1 : wp.nseg);
-  return launch_gemm(GEMM_TN, EPI_F32_ACC, g, st);
+  hipStream_t run_on = now ? sd : st;
+  SiteTimer t(s, site, run_on, now ? 1 : wp.nseg);
+  return launch_gemm(GEMM_TN, EPI_F32_ACC, g, run_on);
 }
 
 // One layer forward.  y == nullptr: stop after the activations backward needs
@@ -397,7 +402,7 @@ hipError_t stream_order(hipStream_t from, hipStream_t to, hipEvent_t ev) {
 // rewritten (dbig, by attention backward) and at the end of the layer (workspace and, with recompute, the
 // shared activation working set are reused by the next layer).
 hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, int beta, const BwdBufs& bb,
-                          const WgradPlan& wp, hipStream_t st, hipStream_t sd) {
+                          const WgradPlan& wp, hipStream_t st, hipStream_t sd, bool fork_ok) {
   const LayerPtrs p = layer_ptrs(s, layer);
   const int T = s->T, h = s->h, hl = s->hl, F = s->F, B = s->cfg.microbatch_size, S = s->cfg.seq_len;
   const int Fu = s->llama ? 2 * F : F;
@@ -419,7 +424,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
 
   // second MLP matrix: dW2 += g^T dy ; input gradient of the activation
   TRY(stream_order(st, sd, ev[0]));  // dy is complete
-  TRY(wgrad(s, SITE_FC2_WGRAD, layer, WG_FC2, wp, a.g, dy, p.g_w2, F, h, sd));
+  TRY(wgrad(s, SITE_FC2_WGRAD, layer, WG_FC2, wp, a.g, dy, p.g_w2, F, h, st, sd));
   if (!s->llama) {
     TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, du, F, T, F, h, nullptr, a.u, F, nullptr, 0, st));  // du
     TRY(stream_order(st, sd, ev[1]));
@@ -430,7 +435,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
     TIMED(SITE_SWIGLU_BWD, launch_swiglu_bwd(dsm, a.u, du, T, F, st));                                                       // d(gate|up)
     TRY(stream_order(st, sd, ev[1]));
   }
-  TRY(wgrad(s, SITE_FC1_WGRAD, layer, WG_FC1, wp, a.c, du, p.g_w1, h, Fu, sd));
+  TRY(wgrad(s, SITE_FC1_WGRAD, layer, WG_FC1, wp, a.c, du, p.g_w1, h, Fu, st, sd));
   TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, du, Fu, p.w1, Fu, dsm, h, T, h, Fu, nullptr, nullptr, 0, nullptr, 0, st));  // dc
   if (sd != st) TRY(hipEventRecord(ev[2], sd));  // the side stream is done with du
   // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
@@ -439,19 +444,19 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n2, nb, h, p.g_ln2_g, beta, sd));
   else ON_SIDE(SITE_COLSUM, launch_colsum_finish3(part_n2, nb, h, p.g_ln2_g, p.g_ln2_b, p.g_b2, beta, sd));
   // output projection
-  TRY(wgrad(s, SITE_WO_WGRAD, layer, WG_WO, wp, a.o, dmid, p.g_wo, hl, h, sd));
+  TRY(wgrad(s, SITE_WO_WGRAD, layer, WG_WO, wp, a.o, dmid, p.g_wo, hl, h, st, sd));
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
   // attention (where dqkv shares its buffer with du: wait until the first MLP matrix's weight gradient has read it)
   if (sd != st && dqkv == du) TRY(hipStreamWaitEvent(st, ev[2], 0));
   const AttnBwdFork fk = {s->side2, ev[7], ev[8]};
-  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dqkv, delta, B, S, s->nh, s->d, s->causal, st, (sd != st && !getenv("AH_NO_ATTN_FORK")) ? &fk : nullptr));
+  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dqkv, delta, B, S, s->nh, s->d, s->causal, st, fork_ok ? &fk : nullptr));
   if (s->llama) TIMED(SITE_ROPE, launch_rope(dqkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
   TRY(stream_order(st, sd, ev[4]));
   if (!s->llama) {
     ON_SIDE(SITE_COLSUM, launch_colsum_partial(dqkv, T, 3 * hl, 3 * hl, part_bqkv, sd));
     ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_bqkv, cb, 3 * hl, p.g_bqkv, beta, sd));
   }
-  TRY(wgrad(s, SITE_QKV_WGRAD, layer, WG_QKV, wp, a.a, dqkv, p.g_wqkv, h, 3 * hl, sd));
+  TRY(wgrad(s, SITE_QKV_WGRAD, layer, WG_QKV, wp, a.a, dqkv, p.g_wqkv, h, 3 * hl, st, sd));
   TRY(gemm(s, SITE_QKV_DGRAD, GEMM_NT, EPI_BF16, dqkv, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
   // first norm backward; dx = dx_mid + norm_bwd(da); column sums give d(gain), d(offset), d(bo)
   TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part_n1, T, h, st));
@@ -514,10 +519,10 @@ hipError_t flush_wgrads(ah_stage* s, hipStream_t st) {
   const int h = s->h, hl = s->hl, F = s->F, Fu = s->llama ? 2 * F : F;
   for (int l = s->L - 1; l >= 0; l--) {
     const LayerPtrs p = layer_ptrs(s, l);
-    TRY(wgrad(s, SITE_FC2_WGRAD, l, WG_FC2, wp, nullptr, nullptr, p.g_w2, F, h, st));
-    TRY(wgrad(s, SITE_FC1_WGRAD, l, WG_FC1, wp, nullptr, nullptr, p.g_w1, h, Fu, st));
-    TRY(wgrad(s, SITE_WO_WGRAD, l, WG_WO, wp, nullptr, nullptr, p.g_wo, hl, h, st));
-    TRY(wgrad(s, SITE_QKV_WGRAD, l, WG_QKV, wp, nullptr, nullptr, p.g_wqkv, h, 3 * hl, st));
+    TRY(wgrad(s, SITE_FC2_WGRAD, l, WG_FC2, wp, nullptr, nullptr, p.g_w2, F, h, st, st));
+    TRY(wgrad(s, SITE_FC1_WGRAD, l, WG_FC1, wp, nullptr, nullptr, p.g_w1, h, Fu, st, st));
+    TRY(wgrad(s, SITE_WO_WGRAD, l, WG_WO, wp, nullptr, nullptr, p.g_wo, hl, h, st, st));
+    TRY(wgrad(s, SITE_QKV_WGRAD, l, WG_QKV, wp, nullptr, nullptr, p.g_wqkv, h, 3 * hl, st, st));
   }
   for (int i = 0; i < n; i++) s->busy[s->pend_slots[i]] = 0;
   s->pend_slots.clear();
@@ -546,7 +551,11 @@ hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipSt
   const void* cur = dy;
   TRY(ensure_side(s));
   // per-site timing wants one kernel at a time: a trace keeps everything on the caller's stream
-  const hipStream_t sd = (s->side_ready && !s->tracing) ? s->side : st;
+  const bool streams_ok = s->side_ready && !s->tracing;
+  // With every matrix deferred only the small reductions would be left for the side stream, and beside the main
+  // chain they cost more than they hide (75.4 vs 75.1 ms per step): everything stays on the caller's stream then.
+  const bool all_deferred = deferred && s->defer_matrix[0] && s->defer_matrix[1] && s->defer_matrix[2] && s->defer_matrix[3];
+  const hipStream_t sd = (streams_ok && !all_deferred) ? s->side : st;
   if (deferred) {  // the caller may reuse dy once this call's work has run: keep a copy for the deferred product
     char* keep;
     (void)pend_bufs(s, pos, s->L - 1, &keep);
@@ -567,7 +576,7 @@ hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipSt
         out = next_dy;
       }
     }
-    TRY(layer_backward(s, l, a, cur, out, beta, bb, wp, st, sd));
+    TRY(layer_backward(s, l, a, cur, out, beta, bb, wp, st, sd, streams_ok));
     cur = out;
     if (ev) TRY(hipEventRecord(ev[l], st));
   }
