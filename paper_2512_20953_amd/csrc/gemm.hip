@@ -499,6 +499,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < 8; i++) bv[i] = bf2f(b[i]);
   }
+  float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // EPI_GELU_BWD: this lane's column sums over the current 64-row slab
+  const bool want_colsum = EPI == EPI_GELU_BWD && g.colsum_part != nullptr;
 #pragma unroll
   for (int tm = 0; tm < TM; tm++) {
     const int mbase = m0 + wm * WM + tm * 32 + row0;
@@ -557,6 +559,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < 8; i++) o[i] = f2bf(v[i]);
         *(bf16x8*)((bf16*)g.C + m * g.ldc + n) = o;
+        if (EPI == EPI_GELU_BWD) {
+#pragma unroll
+          for (int i = 0; i < 8; i++) cs[i] += bf2f(o[i]);
+        }
         if (EPI == EPI_GELU) {
           bf16x8 o2;
 #pragma unroll
@@ -567,6 +573,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));  // strip reads are in registers before the next 32 rows overwrite it
     __builtin_amdgcn_wave_barrier();
+    if (EPI == EPI_GELU_BWD && (tm & 1)) {
+      // two strips = one 64-row slab: lanes that share a column piece (lane % PPR) add up, the first PPR lanes write
+      if (want_colsum) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+#pragma unroll
+          for (int off = PPR; off < 64; off <<= 1) cs[i] += __shfl_xor(cs[i], off);
+        }
+        if (lane < PPR) {
+          float* dst = g.colsum_part + (size_t)((m0 + wm * WM + tm * 32) >> 6) * g.ld_colsum + n;
+          *(f32x4*)dst = f32x4{cs[0], cs[1], cs[2], cs[3]};
+          *(f32x4*)(dst + 4) = f32x4{cs[4], cs[5], cs[6], cs[7]};
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; i++) cs[i] = 0.f;
+    }
   }
 }
 
@@ -708,6 +731,7 @@ GemmArgs column_range(GemmLayout layout, const GemmArgs& a, int c0, int n) {
   if (a.C2) b.C2 = (bf16*)a.C2 + c0;
   if (a.bias) b.bias = (const bf16*)a.bias + c0;
   if (a.aux) b.aux = (const bf16*)a.aux + c0;
+  if (a.colsum_part) b.colsum_part = a.colsum_part + c0;
   if (layout == GEMM_NT) {
     b.B = (const bf16*)a.B + (size_t)c0 * a.ldb;  // B is [N, K]
   } else {

@@ -31,6 +31,10 @@ struct GemmArgs {
   // TN only: the k axis may be the concatenation of n_seg pieces of seg_k rows each (K = n_seg * seg_k), piece i
   // of A starting at segA[i] and of B at segB[i] (same leading dimensions).  n_seg == 0: one piece, A and B.
   int seg_k, n_seg;
+  // EPI_GELU_BWD only, optional: column sums of the (bf16-rounded) output over each slab of 64 rows are written
+  // to colsum_part[m / 64][n] (leading dimension ld_colsum), for the bias gradient.  Needs M % 64 == 0 (it is).
+  float* colsum_part;
+  int ld_colsum;
   const void* segA[kMaxGemmSegments];
   const void* segB[kMaxGemmSegments];
 };

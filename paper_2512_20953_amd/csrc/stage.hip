@@ -312,8 +312,9 @@ ActPtrs act_ptrs(const ah_stage* s, int slot, int layer) {
   } while (0)
 
 hipError_t gemm(ah_stage* s, int site, GemmLayout lay, GemmEpilogue epi, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N,
-                int K, const void* bias, const void* aux, int ld_aux, void* C2, int beta, hipStream_t st) {
+                int K, const void* bias, const void* aux, int ld_aux, void* C2, int beta, hipStream_t st, float* colsum_part = nullptr) {
   GemmArgs g = {};
+  g.colsum_part = colsum_part; g.ld_colsum = N;
   g.A = A; g.B = B; g.C = C; g.C2 = C2; g.bias = bias; g.aux = aux;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ld_aux = ld_aux; g.M = M; g.N = N; g.K = K; g.beta = beta;
   SiteTimer t(s, site, st);
@@ -426,10 +427,10 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   TRY(stream_order(st, sd, ev[0]));  // dy is complete
   TRY(wgrad(s, SITE_FC2_WGRAD, layer, WG_FC2, wp, a.g, dy, p.g_w2, F, h, st, sd));
   if (!s->llama) {
-    TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, du, F, T, F, h, nullptr, a.u, F, nullptr, 0, st));  // du
+    // du, and as a by-product of its epilogue the column sums of du per 64-row slab (for db1)
+    TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, du, F, T, F, h, nullptr, a.u, F, nullptr, 0, st, part_b1));
     TRY(stream_order(st, sd, ev[1]));
-    ON_SIDE(SITE_COLSUM, launch_colsum_partial(du, T, F, F, part_b1, sd));
-    ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_b1, cb, F, p.g_b1, beta, sd));
+    ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_b1, T / 64, F, p.g_b1, beta, sd));
   } else {
     TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_BF16, dy, h, p.w2, h, dsm, F, T, F, h, nullptr, nullptr, 0, nullptr, 0, st));  // dm
     TIMED(SITE_SWIGLU_BWD, launch_swiglu_bwd(dsm, a.u, du, T, F, st));                                                       // d(gate|up)
