@@ -157,13 +157,14 @@ int ah_stage_forward(ah_stage_t* st, int slot, const void* x, void* y, void* hip
  * [B*S, hidden], written.  Adds every parameter's gradient into the fp32
  * gradient buffer (plain sum over micro-batches, no 1/K), or overwrites it if
  * this is the first backward after ah_stage_zero_grads, and frees the slot.
- * With wgrad_group G > 1 only the vector gradients (biases, gains, offsets) are
- * added at once; the slot stays occupied, and the matrices' gradients follow
- * when the G-th micro-batch of the group has had its backward (that call takes
- * them for the whole group and frees all G slots) or at ah_stage_flush_grads. */
+ * With wgrad_group G > 1 the slot stays occupied and the gradient buffer is
+ * brought up to date when the G-th micro-batch of the group has had its
+ * backward (that call takes the group's gradients and frees all G slots) or
+ * at ah_stage_flush_grads; in between it may hold any mixture of old and new
+ * sums (small matrices are still added per micro-batch). */
 int ah_stage_backward(ah_stage_t* st, int slot, const void* dy, void* dx, void* hip_stream);
 
-/* Takes the weight gradients of the micro-batches whose backward has run but
+/* Takes the gradients of the micro-batches whose backward has run but
  * whose group is incomplete (wgrad_group > 1 and a micro-batch count that is
  * not a multiple of it), on `hip_stream`, and frees their slots.  After it the
  * gradient buffer holds the full sums, in stream order.  No-op when nothing
@@ -172,7 +173,7 @@ int ah_stage_flush_grads(ah_stage_t* st, void* hip_stream);
 
 /* The fp32 gradient buffer (device pointer into the caller's `grads`) and its
  * element count; layout per ah_stage_param_layout.  With wgrad_group > 1 the
- * matrices are complete once every group has been taken (see above). */
+ * sums are complete once every group has been taken (see above). */
 int ah_stage_grads(ah_stage_t* st, float** dev_ptr, uint64_t* n_elems);
 
 /* Starts a new accumulation: the next ah_stage_backward overwrites instead of

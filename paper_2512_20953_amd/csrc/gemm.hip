@@ -583,6 +583,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
         }
         if (lane < PPR) {
           float* dst = g.colsum_part + (size_t)((m0 + wm * WM + tm * 32) >> 6) * g.ld_colsum + n;
+          if (g.colsum_acc) {
+            const f32x4 o0 = *(const f32x4*)dst, o1 = *(const f32x4*)(dst + 4);
+#pragma unroll
+            for (int i = 0; i < 4; i++) { cs[i] += o0[i]; cs[4 + i] += o1[i]; }
+          }
           *(f32x4*)dst = f32x4{cs[0], cs[1], cs[2], cs[3]};
           *(f32x4*)(dst + 4) = f32x4{cs[4], cs[5], cs[6], cs[7]};
         }

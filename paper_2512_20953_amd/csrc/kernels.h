@@ -34,7 +34,7 @@ struct GemmArgs {
   // EPI_GELU_BWD only, optional: column sums of the (bf16-rounded) output over each slab of 64 rows are written
   // to colsum_part[m / 64][n] (leading dimension ld_colsum), for the bias gradient.  Needs M % 64 == 0 (it is).
   float* colsum_part;
-  int ld_colsum;
+  int ld_colsum, colsum_acc;  // colsum_acc != 0: added to what is there
   const void* segA[kMaxGemmSegments];
   const void* segB[kMaxGemmSegments];
 };
@@ -58,16 +58,17 @@ hipError_t launch_attention_bwd(const void* qkv, const void* o, const float* lse
 // a = norm(x) * gamma (+ beta); stats[2*T] = (mean, rstd) per row (RMS: mean slot unused = 0)
 hipError_t launch_norm_fwd(bool rms, const void* x, const void* gamma, const void* beta, void* a, float* stats,
                            int T, int h, float eps, hipStream_t s);
-// dx = dres + norm_bwd(da);  partial column sums of (da*xhat, da, dres) go to `part` ([3][nblk][h] fp32)
+// dx = dres + norm_bwd(da);  partial column sums of (da*xhat, da, dres) go to `part` ([3][nblk][h] fp32),
+// written, or with acc != 0 added to what is there (a group of micro-batches sharing one set of partial sums)
 hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float* stats, const void* gamma,
-                           const void* dres, void* dx, float* part, int T, int h, hipStream_t s);
+                           const void* dres, void* dx, float* part, int T, int h, hipStream_t s, int acc = 0);
 int norm_bwd_blocks(int T);
 // g[c] = beta * g[c] + sum_b part[b][c]
 hipError_t launch_colsum_finish(const float* part, int nblk, int n, float* g, int beta, hipStream_t s);
 // the three partial arrays a norm backward leaves in `part` -> three gradient vectors in one launch
 hipError_t launch_colsum_finish3(const float* part, int nblk, int n, float* g0, float* g1, float* g2, int beta, hipStream_t s);
-// partial column sums of a bf16 matrix [T, n] -> part[nblk][n]
-hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* part, hipStream_t s);
+// partial column sums of a bf16 matrix [T, n] -> part[nblk][n] (acc != 0: added to what is there)
+hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* part, hipStream_t s, int acc = 0);
 int colsum_blocks(int T);
 // rotary embedding in place on the Q and K blocks of qkv[T, 3*nh*d]; sign = +1 forward, -1 backward
 hipError_t launch_rope(void* qkv, const float* cos_sin, int T, int S, int nh, int d, float sign, hipStream_t s);

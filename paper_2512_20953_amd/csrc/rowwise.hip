@@ -97,7 +97,7 @@ template <bool RMS, int MAXC>
 __global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ da, const bf16* __restrict__ x,
                                                        const float* __restrict__ stats, const bf16* __restrict__ gamma,
                                                        const bf16* __restrict__ dres, bf16* __restrict__ dx,
-                                                       float* __restrict__ part, int T, int h, int rpb) {
+                                                       float* __restrict__ part, int T, int h, int rpb, int acc) {
   constexpr int RB = MAXC <= 1 ? 4 : (MAXC <= 2 ? 2 : 1);  // rows per batch, bounded by the register file
   constexpr int NWV = NTB / 64;
   constexpr bool PIPE = MAXC <= 2;  // wider rows (hidden > 8192) leave no registers for a second batch, and spill a few
@@ -219,7 +219,10 @@ __global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ 
       float* p1 = part + ((size_t)1 * nblk + blockIdx.x) * h + c * 8;
       float* p2 = part + ((size_t)2 * nblk + blockIdx.x) * h + c * 8;
 #pragma unroll
-      for (int j = 0; j < 8; j++) { p0[j] = s_g[i][j]; p1[j] = s_b[i][j]; p2[j] = s_r[i][j]; }
+      for (int j = 0; j < 8; j++) {
+        if (acc) { p0[j] += s_g[i][j]; p1[j] += s_b[i][j]; p2[j] += s_r[i][j]; }  // on top of earlier micro-batches' partial sums
+        else { p0[j] = s_g[i][j]; p1[j] = s_b[i][j]; p2[j] = s_r[i][j]; }
+      }
     }
   }
 }
@@ -230,7 +233,7 @@ __global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ 
 // meet in LDS and leave as one row of part[nblk][n].
 constexpr int CS_ROWS = 64;  // rows per block
 __global__ __launch_bounds__(NT) void colsum_partial_kernel(const bf16* __restrict__ m, int T, int n, int ld,
-                                                            float* __restrict__ part) {
+                                                            float* __restrict__ part, int acc) {
   __shared__ float red[3][512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = blockIdx.x * 512 + lane * 8;
@@ -252,7 +255,10 @@ __global__ __launch_bounds__(NT) void colsum_partial_kernel(const bf16* __restri
   if (wave == 0 && col < n) {
     float* p = part + (size_t)blockIdx.y * n + col;
 #pragma unroll
-    for (int j = 0; j < 8; j++) p[j] = s[j] + red[0][lane * 8 + j] + red[1][lane * 8 + j] + red[2][lane * 8 + j];
+    for (int j = 0; j < 8; j++) {
+      const float v = s[j] + red[0][lane * 8 + j] + red[1][lane * 8 + j] + red[2][lane * 8 + j];
+      p[j] = acc ? p[j] + v : v;
+    }
   }
 }
 
@@ -360,11 +366,11 @@ void norm_fwd_go(const void* x, const void* gamma, const void* beta, void* a, fl
 }
 template <bool RMS, int MAXC>
 void norm_bwd_go(const void* da, const void* x, const float* stats, const void* gamma, const void* dres, void* dx, float* part,
-                 int T, int h, hipStream_t s) {
+                 int T, int h, int acc, hipStream_t s) {
   const int nblk = norm_bwd_blocks(T);
   const int rpb = (T + nblk - 1) / nblk;
   hipLaunchKernelGGL((norm_bwd_kernel<RMS, MAXC>), dim3(nblk), dim3(NTB), 0, s, (const bf16*)da, (const bf16*)x, stats,
-                     (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, part, T, h, rpb);
+                     (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, part, T, h, rpb, acc);
 }
 }  // namespace
 
@@ -395,13 +401,13 @@ hipError_t launch_norm_fwd(bool rms, const void* x, const void* gamma, const voi
 #define AH_BWD_BY_CHUNKS(RMS)                                                                        \
   do {                                                                                               \
     const int nc = (h + 4095) / 4096;                                                                \
-    if (nc <= 1) norm_bwd_go<RMS, 1>(da, x, stats, gamma, dres, dx, part, T, h, s);                  \
-    else if (nc == 2) norm_bwd_go<RMS, 2>(da, x, stats, gamma, dres, dx, part, T, h, s);             \
-    else norm_bwd_go<RMS, 4>(da, x, stats, gamma, dres, dx, part, T, h, s);                          \
+    if (nc <= 1) norm_bwd_go<RMS, 1>(da, x, stats, gamma, dres, dx, part, T, h, acc, s);             \
+    else if (nc == 2) norm_bwd_go<RMS, 2>(da, x, stats, gamma, dres, dx, part, T, h, acc, s);        \
+    else norm_bwd_go<RMS, 4>(da, x, stats, gamma, dres, dx, part, T, h, acc, s);                     \
   } while (0)
 
 hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float* stats, const void* gamma, const void* dres,
-                           void* dx, float* part, int T, int h, hipStream_t s) {
+                           void* dx, float* part, int T, int h, hipStream_t s, int acc) {
   if (h % 8 || h > 16384) return hipErrorInvalidValue;
   if (rms) AH_BWD_BY_CHUNKS(true);
   else AH_BWD_BY_CHUNKS(false);
@@ -422,9 +428,9 @@ hipError_t launch_colsum_finish3(const float* part, int nblk, int n, float* g0, 
 
 int colsum_blocks(int T) { return (T + CS_ROWS - 1) / CS_ROWS; }
 
-hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* part, hipStream_t s) {
+hipError_t launch_colsum_partial(const void* m, int T, int n, int ld, float* part, hipStream_t s, int acc) {
   if (n % 8) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(colsum_partial_kernel, dim3((n + 511) / 512, colsum_blocks(T)), dim3(NT), 0, s, (const bf16*)m, T, n, ld, part);
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3((n + 511) / 512, colsum_blocks(T)), dim3(NT), 0, s, (const bf16*)m, T, n, ld, part, acc);
   return hipGetLastError();
 }
 

@@ -28,12 +28,14 @@ struct ActLayout {
 };
 
 struct Workspace {
-  size_t d0, d1, dmid, dbig, dsm, delta, part_n2, part_n1, part_b1, part_bqkv, rope, prof_x, prof_dy, prof_y, prof_dx, layer_ws, pend, bytes;
+  size_t d0, d1, dmid, dbig, dsm, delta, part_n2, part_n1, part_b1, part_bqkv, rope, prof_x, prof_dy, prof_y, prof_dx, layer_ws, pend, vec_part, bytes;
 };
 
 // Output-gradient operands of one layer's four weight-gradient products, kept per (position in the group, layer)
 // while those products wait for the rest of the group: byte offsets inside one such block.
 struct PendLayout { size_t dy, dmid, du, dqkv, bytes; };
+// Partial sums of one layer's vector gradients, shared by the micro-batches of a group (byte offsets in its block).
+struct VecPartLayout { size_t n2, n1, b1, bqkv, bytes; };
 
 }  // namespace
 
@@ -58,6 +60,7 @@ struct ah_stage {
   bool defer_matrix[4];         // by WgradWhich: small outputs stay undeferred (see plan())
   bool force_immediate;         // the profiler's per-layer timing runs undeferred
   PendLayout pend;
+  VecPartLayout vpart;
   std::vector<int> pend_slots;  // slots of the micro-batches waiting, in backward order
   bool rope_ready;
   // optional per-call-site timing (ah_stage_trace_begin / _end)
@@ -198,6 +201,15 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
   s->pend.bytes = o;
   o = before_pend;
   w.pend = take(s->group > 1 ? (size_t)s->group * s->L * s->pend.bytes : 0);
+  const size_t before_vec = o;
+  o = 0;
+  s->vpart.n2 = take((size_t)3 * norm_bwd_blocks(s->T) * h * 4);
+  s->vpart.n1 = take((size_t)3 * norm_bwd_blocks(s->T) * h * 4);
+  s->vpart.b1 = take(s->llama ? 0 : (size_t)colsum_blocks(s->T) * F * 4);
+  s->vpart.bqkv = take(s->llama ? 0 : (size_t)colsum_blocks(s->T) * 3 * hl * 4);
+  s->vpart.bytes = o;
+  o = before_vec;
+  w.vec_part = take(s->group > 1 ? (size_t)s->L * s->vpart.bytes : 0);
   w.bytes = o;
 }
 
@@ -312,9 +324,10 @@ ActPtrs act_ptrs(const ah_stage* s, int slot, int layer) {
   } while (0)
 
 hipError_t gemm(ah_stage* s, int site, GemmLayout lay, GemmEpilogue epi, const void* A, int lda, const void* B, int ldb, void* C, int ldc, int M, int N,
-                int K, const void* bias, const void* aux, int ld_aux, void* C2, int beta, hipStream_t st, float* colsum_part = nullptr) {
+                int K, const void* bias, const void* aux, int ld_aux, void* C2, int beta, hipStream_t st, float* colsum_part = nullptr,
+                int colsum_acc = 0) {
   GemmArgs g = {};
-  g.colsum_part = colsum_part; g.ld_colsum = N;
+  g.colsum_part = colsum_part; g.ld_colsum = N; g.colsum_acc = colsum_acc;
   g.A = A; g.B = B; g.C = C; g.C2 = C2; g.bias = bias; g.aux = aux;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ld_aux = ld_aux; g.M = M; g.N = N; g.K = K; g.beta = beta;
   SiteTimer t(s, site, st);
@@ -339,6 +352,25 @@ BwdBufs pend_bufs(const ah_stage* s, int pos, int layer, char** dy_out) {
 struct WgradPlan { int nseg; int slots[kMaxGemmSegments]; int beta, beta_now; };
 
 enum WgradWhich { WG_FC2, WG_FC1, WG_WO, WG_QKV };
+
+// Where a layer's backward leaves the partial column sums behind its vector gradients (biases, gains, offsets) and
+// what it does with them.  Undeferred: the shared workspace regions, written (acc = 0) and folded into the gradient
+// at once (finish).  Deferred: the layer's own regions, written by the first micro-batch of a group and added to by
+// the others, folded once when the group closes.
+struct VecPlan { float *n2, *n1, *b1, *bqkv; int acc; bool finish; int beta; };
+
+VecPlan vec_plan(const ah_stage* s, int layer, bool deferred, int pos, bool closes, int beta_now, int beta_group) {
+  char* wsb = (char*)s->bufs.workspace;
+  if (!deferred)
+    return {(float*)(wsb + s->ws.part_n2), (float*)(wsb + s->ws.part_n1), (float*)(wsb + s->ws.part_b1), (float*)(wsb + s->ws.part_bqkv),
+            0, true, beta_now};
+  char* b = wsb + s->ws.vec_part + (size_t)layer * s->vpart.bytes;
+  return {(float*)(b + s->vpart.n2), (float*)(b + s->vpart.n1), (float*)(b + s->vpart.b1), (float*)(b + s->vpart.bqkv),
+          pos > 0 ? 1 : 0, closes, beta_group};
+}
+
+// Folds one layer's partial sums into its vector gradients (the four reductions that end a layer's backward).
+hipError_t finish_vectors(ah_stage* s, int layer, const VecPlan& vp, hipStream_t st);
 
 // One weight-gradient product C[M, N] (+)= sum over the plan's micro-batches of act^T dY.
 // A product over one micro-batch goes to `sd` (the side stream: beside the rest of backward it hides its tail and
@@ -402,15 +434,15 @@ hipError_t stream_order(hipStream_t from, hipStream_t to, hipEvent_t ev) {
 // after its producer on st, st waits for the side stream before a buffer the side stream still reads is
 // rewritten (dbig, by attention backward) and at the end of the layer (workspace and, with recompute, the
 // shared activation working set are reused by the next layer).
-hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, int beta, const BwdBufs& bb,
+hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, const VecPlan& vp, const BwdBufs& bb,
                           const WgradPlan& wp, hipStream_t st, hipStream_t sd, bool fork_ok) {
   const LayerPtrs p = layer_ptrs(s, layer);
   const int T = s->T, h = s->h, hl = s->hl, F = s->F, B = s->cfg.microbatch_size, S = s->cfg.seq_len;
   const int Fu = s->llama ? 2 * F : F;
   char* wsb = (char*)s->bufs.workspace;
   char *dmid = bb.dmid, *du = bb.du, *dqkv = bb.dqkv, *dsm = wsb + s->ws.dsm;
-  float *part_n2 = (float*)(wsb + s->ws.part_n2), *part_n1 = (float*)(wsb + s->ws.part_n1);
-  float *part_b1 = (float*)(wsb + s->ws.part_b1), *part_bqkv = (float*)(wsb + s->ws.part_bqkv);
+  float *part_n2 = vp.n2, *part_n1 = vp.n1, *part_b1 = vp.b1, *part_bqkv = vp.bqkv;
+  const int beta = vp.beta;
   float* delta = (float*)(wsb + s->ws.delta);
   const int nb = norm_bwd_blocks(T), cb = colsum_blocks(T);
   const bool rms = s->llama;
@@ -428,9 +460,9 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   TRY(wgrad(s, SITE_FC2_WGRAD, layer, WG_FC2, wp, a.g, dy, p.g_w2, F, h, st, sd));
   if (!s->llama) {
     // du, and as a by-product of its epilogue the column sums of du per 64-row slab (for db1)
-    TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, du, F, T, F, h, nullptr, a.u, F, nullptr, 0, st, part_b1));
+    TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_GELU_BWD, dy, h, p.w2, h, du, F, T, F, h, nullptr, a.u, F, nullptr, 0, st, part_b1, vp.acc));
     TRY(stream_order(st, sd, ev[1]));
-    ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_b1, T / 64, F, p.g_b1, beta, sd));
+    if (vp.finish) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_b1, T / 64, F, p.g_b1, beta, sd));
   } else {
     TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_BF16, dy, h, p.w2, h, dsm, F, T, F, h, nullptr, nullptr, 0, nullptr, 0, st));  // dm
     TIMED(SITE_SWIGLU_BWD, launch_swiglu_bwd(dsm, a.u, du, T, F, st));                                                       // d(gate|up)
@@ -440,10 +472,12 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, du, Fu, p.w1, Fu, dsm, h, T, h, Fu, nullptr, nullptr, 0, nullptr, 0, st));  // dc
   if (sd != st) TRY(hipEventRecord(ev[2], sd));  // the side stream is done with du
   // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
-  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part_n2, T, h, st));
+  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part_n2, T, h, st, vp.acc));
   TRY(stream_order(st, sd, ev[3]));
-  if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n2, nb, h, p.g_ln2_g, beta, sd));
-  else ON_SIDE(SITE_COLSUM, launch_colsum_finish3(part_n2, nb, h, p.g_ln2_g, p.g_ln2_b, p.g_b2, beta, sd));
+  if (vp.finish) {
+    if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n2, nb, h, p.g_ln2_g, beta, sd));
+    else ON_SIDE(SITE_COLSUM, launch_colsum_finish3(part_n2, nb, h, p.g_ln2_g, p.g_ln2_b, p.g_b2, beta, sd));
+  }
   // output projection
   TRY(wgrad(s, SITE_WO_WGRAD, layer, WG_WO, wp, a.o, dmid, p.g_wo, hl, h, st, sd));
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
@@ -454,16 +488,18 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   if (s->llama) TIMED(SITE_ROPE, launch_rope(dqkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
   TRY(stream_order(st, sd, ev[4]));
   if (!s->llama) {
-    ON_SIDE(SITE_COLSUM, launch_colsum_partial(dqkv, T, 3 * hl, 3 * hl, part_bqkv, sd));
-    ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_bqkv, cb, 3 * hl, p.g_bqkv, beta, sd));
+    ON_SIDE(SITE_COLSUM, launch_colsum_partial(dqkv, T, 3 * hl, 3 * hl, part_bqkv, sd, vp.acc));
+    if (vp.finish) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_bqkv, cb, 3 * hl, p.g_bqkv, beta, sd));
   }
   TRY(wgrad(s, SITE_QKV_WGRAD, layer, WG_QKV, wp, a.a, dqkv, p.g_wqkv, h, 3 * hl, st, sd));
   TRY(gemm(s, SITE_QKV_DGRAD, GEMM_NT, EPI_BF16, dqkv, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
   // first norm backward; dx = dx_mid + norm_bwd(da); column sums give d(gain), d(offset), d(bo)
-  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part_n1, T, h, st));
+  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part_n1, T, h, st, vp.acc));
   TRY(stream_order(st, sd, ev[5]));
-  if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n1, nb, h, p.g_ln1_g, beta, sd));
-  else ON_SIDE(SITE_COLSUM, launch_colsum_finish3(part_n1, nb, h, p.g_ln1_g, p.g_ln1_b, p.g_bo, beta, sd));
+  if (vp.finish) {
+    if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n1, nb, h, p.g_ln1_g, beta, sd));
+    else ON_SIDE(SITE_COLSUM, launch_colsum_finish3(part_n1, nb, h, p.g_ln1_g, p.g_ln1_b, p.g_bo, beta, sd));
+  }
   TRY(stream_order(sd, st, ev[6]));  // join
 #undef ON_SIDE
   return hipSuccess;
@@ -509,7 +545,23 @@ hipError_t stage_forward(ah_stage* s, int slot, const void* x, void* y, hipStrea
   return hipSuccess;
 }
 
-// The weight-gradient products of every layer over the micro-batches waiting in pend_slots; frees their slots.
+hipError_t finish_vectors(ah_stage* s, int layer, const VecPlan& vp, hipStream_t st) {
+  const LayerPtrs p = layer_ptrs(s, layer);
+  const int T = s->T, h = s->h, hl = s->hl, F = s->F, nb = norm_bwd_blocks(T), cb = colsum_blocks(T);
+  if (s->llama) {
+    TIMED(SITE_COLSUM, launch_colsum_finish(vp.n2, nb, h, p.g_ln2_g, vp.beta, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish(vp.n1, nb, h, p.g_ln1_g, vp.beta, st));
+  } else {
+    TIMED(SITE_COLSUM, launch_colsum_finish(vp.b1, T / 64, F, p.g_b1, vp.beta, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish3(vp.n2, nb, h, p.g_ln2_g, p.g_ln2_b, p.g_b2, vp.beta, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish(vp.bqkv, cb, 3 * hl, p.g_bqkv, vp.beta, st));
+    TIMED(SITE_COLSUM, launch_colsum_finish3(vp.n1, nb, h, p.g_ln1_g, p.g_ln1_b, p.g_bo, vp.beta, st));
+  }
+  return hipSuccess;
+}
+
+// The gradients still owed to the micro-batches waiting in pend_slots (every layer's deferred weight-gradient
+// products over them, and the vector gradients from the layers' partial sums); frees their slots.
 hipError_t flush_wgrads(ah_stage* s, hipStream_t st) {
   const int n = (int)s->pend_slots.size();
   if (n == 0) return hipSuccess;
@@ -524,6 +576,7 @@ hipError_t flush_wgrads(ah_stage* s, hipStream_t st) {
     TRY(wgrad(s, SITE_FC1_WGRAD, l, WG_FC1, wp, nullptr, nullptr, p.g_w1, h, Fu, st, st));
     TRY(wgrad(s, SITE_WO_WGRAD, l, WG_WO, wp, nullptr, nullptr, p.g_wo, hl, h, st, st));
     TRY(wgrad(s, SITE_QKV_WGRAD, l, WG_QKV, wp, nullptr, nullptr, p.g_wqkv, h, 3 * hl, st, st));
+    TRY(finish_vectors(s, l, vec_plan(s, l, true, n, true, 0, wp.beta), st));
   }
   for (int i = 0; i < n; i++) s->busy[s->pend_slots[i]] = 0;
   s->pend_slots.clear();
@@ -577,7 +630,8 @@ hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipSt
         out = next_dy;
       }
     }
-    TRY(layer_backward(s, l, a, cur, out, beta, bb, wp, st, sd, streams_ok));
+    const VecPlan vp = vec_plan(s, l, deferred, pos, closes_group, beta, wp.beta);
+    TRY(layer_backward(s, l, a, cur, out, vp, bb, wp, st, sd, streams_ok));
     cur = out;
     if (ev) TRY(hipEventRecord(ev[l], st));
   }

@@ -154,7 +154,7 @@ def test_benchmark_iteration_properties():
 def test_benchmark_iteration_with_deferred_weight_gradients():
     """gpt7b_tp2 as bench.py runs it by default (one weight-gradient product per layer matrix over all 8
     micro-batches, 32768 tokens on the k axis) against the per-micro-batch accumulation: same y and dx bit for
-    bit, same vector gradients bit for bit, matrices up to fp32 summation order; bit-reproducible; and the
+    bit, gradients up to fp32 summation order; bit-reproducible; and the
     profiler's iteration (which rotates the slots itself) runs in this mode."""
     w = SI.WORKLOADS["gpt7b_tp2"]
     T, K = w["mb"] * w["seq"], w["n_mb"]
@@ -186,9 +186,7 @@ def test_benchmark_iteration_with_deferred_weight_gradients():
     (y0, dx0, s0), (y1, dx1, s1) = results
     assert all(torch.equal(a, b) for a, b in zip(y0 + dx0, y1 + dx1))
     for l in range(w["n_layers"]):
-        for name in ("ln1_g", "ln1_b", "bqkv", "bo", "ln2_g", "ln2_b", "b1", "b2"):
-            assert torch.equal(s0.grad_view(l, name), s1.grad_view(l, name)), (l, name)
-        for name in ("wqkv", "wo", "w1", "w2"):
+        for name in ("ln1_g", "ln1_b", "bqkv", "bo", "ln2_g", "ln2_b", "b1", "b2", "wqkv", "wo", "w1", "w2"):
             a, b = s0.grad_view(l, name).double(), s1.grad_view(l, name).double()
             err = ((a - b).norm() / a.norm()).item()
             assert err <= 2e-6, (l, name, err)

@@ -76,8 +76,9 @@ def test_recompute_is_bit_identical(name):
 def test_deferred_weight_gradients(name, n_mb, group):
     """Weight-gradient products taken once per group of micro-batches (full groups, an incomplete last group
     that needs the flush, a group larger than the iteration): against the oracle at the usual gates, and
-    against the undeferred run: y, dx and the vector gradients bit for bit (their path is the same), the
-    matrices up to fp32 summation order."""
+    against the undeferred run: y and dx bit for bit (their path is the same), the gradients up to fp32
+    summation order (a group's sums are formed in the accumulators and in shared partial sums before they
+    reach the gradient buffer)."""
     w = dict(SI.WORKLOADS[name] if name in SI.WORKLOADS else REDUCED[name], n_mb=n_mb)
     st0, ys0, dxs0 = _run_case(w, n_mb)
     st1, ys1, dxs1 = _run_case(w, n_mb, wgrad_group=group)
@@ -85,10 +86,7 @@ def test_deferred_weight_gradients(name, n_mb, group):
     for l in range(w["n_layers"]):
         for pname in SI.draw_layer_params(w, l):
             g0, g1 = st0.grad_view(l, pname), st1.grad_view(l, pname)
-            if g0.dim() == 1:
-                assert torch.equal(g0, g1), (l, pname)
-            else:
-                assert U.rel_l2(U.to_np(g1), U.to_np(g0)) <= 2e-6, (l, pname)
+            assert U.rel_l2(U.to_np(g1), U.to_np(g0)) <= 2e-6, (l, pname)
 
 
 def test_deferred_weight_gradients_slot_rules():
