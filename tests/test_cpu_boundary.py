@@ -116,7 +116,7 @@ def test_gemm_entry_points_refuse_bad_shapes_without_touching_the_device():
 
 def test_deferred_weight_gradient_configuration_and_sizes():
     """wgrad_group: range, its two preconditions, and the workspace it adds (G * layers blocks of the four
-    output-gradient operands), checked against the byte count written out by hand."""
+    output-gradient operands, and per layer the shared partial sums), checked against the byte count written out by hand."""
     base = dict(arch="gpt", n_layers=3, hidden=256, n_heads=4, head_dim=64, ffn=1024, seq=128, mb=2)
     for bad in (dict(wgrad_group=2, max_in_flight=1), dict(wgrad_group=17, max_in_flight=32), dict(wgrad_group=-1),
                 dict(wgrad_group=2, max_in_flight=2, recompute=1)):
@@ -129,5 +129,8 @@ def test_deferred_weight_gradient_configuration_and_sizes():
     assert s0 == s1
     T, h, hl, F = 256, 256, 256, 1024
     block = 2 * T * (h + h + F + 3 * hl)
-    assert s4["workspace_bytes"] - s0["workspace_bytes"] == 4 * 3 * block
+    # plus, per layer, one set of fp32 partial sums for the vector gradients: two norm backward kernels
+    # (3 arrays x 64 blocks x h), db1 and dbqkv (T / 64 slabs x their widths)
+    vec = 2 * 3 * 64 * h * 4 + (T // 64) * F * 4 + (T // 64) * 3 * hl * 4
+    assert s4["workspace_bytes"] - s0["workspace_bytes"] == 4 * 3 * block + 3 * vec
     assert {k: v for k, v in s4.items() if k != "workspace_bytes"} == {k: v for k, v in s0.items() if k != "workspace_bytes"}
