@@ -429,11 +429,13 @@ hipError_t stream_order(hipStream_t from, hipStream_t to, hipEvent_t ev) {
 }
 
 // One layer backward.  `st` carries the chain every later kernel depends on (input gradients, attention,
-// norms); `sd` (the side stream, or st itself) carries the weight-gradient GEMMs and the column-sum
-// reductions, which only the caller's next use of the gradients waits for.  Each side launch is ordered
-// after its producer on st, st waits for the side stream before a buffer the side stream still reads is
-// rewritten (dbig, by attention backward) and at the end of the layer (workspace and, with recompute, the
-// shared activation working set are reused by the next layer).
+// norms) and the weight-gradient products taken over a whole group; `sd` (the side stream, or st itself)
+// carries the per-micro-batch weight-gradient GEMMs and the reductions behind the vector gradients, which only
+// the caller's next use of the gradients waits for.  Each side launch is ordered after its producer on st, st
+// waits for the side stream before a buffer the side stream still reads is rewritten (du, by attention backward,
+// where dqkv shares its buffer) and at the end of the layer (workspace and, with recompute, the shared activation
+// working set are reused by the next layer).  bb: where the intermediate gradients go; wp, vp: what happens to
+// the matrix and vector gradients now (see WgradPlan, VecPlan); fork_ok: attention backward may use side2.
 hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, const VecPlan& vp, const BwdBufs& bb,
                           const WgradPlan& wp, hipStream_t st, hipStream_t sd, bool fork_ok) {
   const LayerPtrs p = layer_ptrs(s, layer);
