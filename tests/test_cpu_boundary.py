@@ -94,6 +94,12 @@ def test_create_refuses_missing_or_misaligned_buffers():
     assert lib.ah_stage_param_layout(h, 1, P.PARAM_INDEX["w2"], ctypes.byref(off), ctypes.byref(r), ctypes.byref(cc)) == 0
     assert (r.value, cc.value) == (1024, 256)
     assert lib.ah_stage_param_layout(h, 2, 0, ctypes.byref(off), ctypes.byref(r), ctypes.byref(cc)) == 1
+    # nothing pending: flushing and restarting the accumulation are host-side no-ops; bad handles and slots are refused
+    assert lib.ah_stage_flush_grads(h, None) == 0
+    assert lib.ah_stage_zero_grads(h, None) == 0
+    assert lib.ah_stage_flush_grads(None, None) == 1
+    assert lib.ah_stage_forward(h, 7, 256, 256, None) == 1      # slot out of range
+    assert lib.ah_stage_backward(h, 0, 256, 256, None) == 3     # no forward in that slot
     assert lib.ah_stage_destroy(h) == 0
 
 
