@@ -51,6 +51,9 @@ REDUCED = {
     # bidirectional attention: 3 query / key blocks with head_dim 128 on a TP shard; 2 blocks with head_dim 64
     "bert_d128_tp2": dict(arch="bert", n_layers=2, hidden=384, n_heads=4, head_dim=128, ffn=1536, seq=384, mb=2, n_mb=2, tp=2, recompute=0),
     "bert_tiny": SI.WORKLOADS["bert_tiny"],
+    # odd multiples of the tile sizes everywhere: 384 rows, hidden 640, 5 heads, FFN 1152 (only 128-wide tiles divide these)
+    "gpt_odd": dict(arch="gpt", n_layers=2, hidden=640, n_heads=5, head_dim=128, ffn=1152, seq=128, mb=3, n_mb=2, tp=1, recompute=0),
+    "llama_odd": dict(arch="llama", n_layers=1, hidden=384, n_heads=6, head_dim=64, ffn=640, seq=384, mb=1, n_mb=3, tp=1, recompute=1),
 }
 
 
@@ -72,7 +75,7 @@ def test_recompute_is_bit_identical(name):
 
 
 @pytest.mark.parametrize("name,n_mb,group", [("tiny", 4, 2), ("tiny", 5, 3), ("gpt_d128_tp2", 3, 3), ("llama_small", 3, 2),
-                                             ("bert_tiny", 2, 16)])
+                                             ("bert_tiny", 2, 16), ("gpt_odd", 3, 2)])
 def test_deferred_weight_gradients(name, n_mb, group):
     """Weight-gradient products taken once per group of micro-batches (full groups, an incomplete last group
     that needs the flush, a group larger than the iteration): against the oracle at the usual gates, and
