@@ -53,6 +53,9 @@ REDUCED = {
     "bert_tiny": SI.WORKLOADS["bert_tiny"],
     # odd multiples of the tile sizes everywhere: 384 rows, hidden 640, 5 heads, FFN 1152 (only 128-wide tiles divide these)
     "gpt_odd": dict(arch="gpt", n_layers=2, hidden=640, n_heads=5, head_dim=128, ffn=1152, seq=128, mb=3, n_mb=2, tp=1, recompute=0),
+    # the widest rows the library accepts (hidden 16384) and a width between the row kernels' chunk sizes (12288)
+    "gpt_widest": dict(arch="gpt", n_layers=1, hidden=16384, n_heads=2, head_dim=128, ffn=256, seq=128, mb=1, n_mb=2, tp=1, recompute=0),
+    "llama_wide": dict(arch="llama", n_layers=1, hidden=12288, n_heads=2, head_dim=64, ffn=128, seq=128, mb=2, n_mb=1, tp=1, recompute=0),
     "llama_odd": dict(arch="llama", n_layers=1, hidden=384, n_heads=6, head_dim=64, ffn=640, seq=384, mb=1, n_mb=3, tp=1, recompute=1),
 }
 
