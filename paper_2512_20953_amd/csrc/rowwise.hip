@@ -98,7 +98,7 @@ __global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ 
                                                        const float* __restrict__ stats, const bf16* __restrict__ gamma,
                                                        const bf16* __restrict__ dres, bf16* __restrict__ dx,
                                                        float* __restrict__ part, int T, int h, int rpb, int acc) {
-  constexpr int RB = MAXC <= 2 ? 2 : 1;  // rows per batch: two keep a 4096-wide row kernel at 125 registers (36.8 us; four rows 39.6, one 38.4)
+  constexpr int RB = MAXC <= 1 ? 2 : 1;  // rows per batch: two keep a 4096-wide row kernel at 125 registers (36.8 us; four rows 39.6, one 38.4)
   constexpr int NWV = NTB / 64;
   constexpr bool PIPE = MAXC <= 2;  // wider rows (hidden > 8192) leave no registers for a second batch, and spill a few
   __shared__ float red[2][NWV][2 * RB];                     // double-buffered: one block barrier per batch
