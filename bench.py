@@ -37,7 +37,7 @@ def model_flops_per_iter(w):
 
 
 def cpu_baseline(w, name):
-    """The oracle as it stands, float32, on a bounded sample: one layer, one sequence, forward + backward."""
+    """The oracle as it stands, float32, on a bounded sample: one layer, two micro-batches, forward + backward."""
     import numpy as np
     from oracle import stage_ref as R
     from synth import stage_inputs as SI
@@ -46,23 +46,29 @@ def cpu_baseline(w, name):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
     except Exception:
         cores = os.cpu_count()
-    ws = dict(w, n_layers=1, mb=1)
+    # one layer, two of the workload's micro-batches: about 10-30 s of numpy on the box's share of host cores
+    ws = dict(w, n_layers=1)
+    reps = 2
     nh, hl, Fl = SI.local_dims(ws)
     cfg = R.StageCfg(ws["arch"], 1, ws["hidden"], nh, ws["head_dim"], Fl, ws["seq"], 1e-6 if ws["arch"] == "llama" else 1e-5)
     rng = np.random.default_rng(0)
     params = [{n: (np.ones(s, np.float32) if k == "one" else np.zeros(s, np.float32) if k == "zero"
                    else (rng.standard_normal(s, dtype=np.float32) * np.float32(0.02)))
                for n, s, k in SI.param_spec(ws["arch"], ws["hidden"], hl, Fl)}]
-    x = rng.standard_normal((ws["seq"], ws["hidden"]), dtype=np.float32)
-    dy = rng.standard_normal((ws["seq"], ws["hidden"]), dtype=np.float32)
+    T = ws["mb"] * ws["seq"]
+    xs = [rng.standard_normal((T, ws["hidden"]), dtype=np.float32) for _ in range(reps)]
+    dys = [rng.standard_normal((T, ws["hidden"]), dtype=np.float32) for _ in range(reps)]
     grads = R.zero_grads_like(params)
     t0 = time.perf_counter()
-    y, caches, _ = R.stage_fwd(cfg, params, x)
-    R.stage_bwd(cfg, params, caches, dy, grads)
+    for x, dy in zip(xs, dys):
+        y, caches, _ = R.stage_fwd(cfg, params, x)
+        R.stage_bwd(cfg, params, caches, dy, grads)
     dt = time.perf_counter() - t0
-    return {"value": ws["seq"] / (dt * w["n_layers"]), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": "workload %s: 1 of %d layers, 1 sequence of %d tokens, forward+backward in float32 numpy, %.1f s; "
-                      "tokens/s = %d / (%d layers x that time)" % (name, w["n_layers"], ws["seq"], dt, ws["seq"], w["n_layers"])}
+    tokens = T * reps
+    return {"value": tokens / (dt * w["n_layers"]), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "workload %s: 1 of %d layers, %d micro-batches of %d x %d tokens, forward+backward with fp32 gradient accumulation "
+                      "in float32 numpy, %.1f s; tokens/s = %d / (%d layers x that time)"
+                      % (name, w["n_layers"], reps, ws["mb"], ws["seq"], dt, tokens, w["n_layers"])}
 
 
 def main():
