@@ -90,7 +90,9 @@ typedef struct {
   int32_t n_microbatches;   /* K of Eq. 1: micro-batches accumulated per iteration (used by ah_stage_profile) */
   int32_t max_in_flight;    /* activation slots: micro-batches whose forward has run and whose backward has not (1F1B: stages - stage index) */
   int32_t recompute;        /* 0: keep every layer's activations; 1: keep layer inputs only and re-run each layer's forward inside backward */
-  int32_t wgrad_group;      /* G.  0 or 1: every ah_stage_backward adds its micro-batch's weight gradients at once.
+  int32_t wgrad_group;      /* G: how the gradient sum over the K micro-batches of an iteration (Section III-A, the
+                             * accumulation behind Eq. 1's K micro-batch terms) is grouped.
+                             * 0 or 1: every ah_stage_backward adds its micro-batch's weight gradients at once.
                              * G > 1 (<= 16, <= max_in_flight, recompute == 0): the weight-gradient products of a
                              * layer are taken once per G micro-batches, over the concatenation of their tokens,
                              * by the G-th backward of each group (or ah_stage_flush_grads): the fp32 gradient
@@ -164,7 +166,8 @@ int ah_stage_forward(ah_stage_t* st, int slot, const void* x, void* y, void* hip
  * sums (small matrices are still added per micro-batch). */
 int ah_stage_backward(ah_stage_t* st, int slot, const void* dy, void* dx, void* hip_stream);
 
-/* Takes the gradients of the micro-batches whose backward has run but
+/* Closes an incomplete group of the gradient accumulation over micro-batches (Section III-A; see wgrad_group).
+ * Takes the gradients of the micro-batches whose backward has run but
  * whose group is incomplete (wgrad_group > 1 and a micro-batch count that is
  * not a multiple of it), on `hip_stream`, and frees their slots.  After it the
  * gradient buffer holds the full sums, in stream order.  No-op when nothing
