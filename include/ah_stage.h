@@ -20,11 +20,11 @@
  *    passed as `hip_stream` (a hipStream_t cast to void*; NULL = the default
  *    stream) and never synchronise.  ah_stage_profile synchronises.
  *    ah_stage_backward may run work that nothing downstream waits for (the
- *    per-micro-batch weight-gradient products, the bias / gain reductions, one
- *    of the two attention-backward kernels) on streams of its own (created on
- *    the first call, at the default priority); they are ordered after the work
- *    they consume and joined back into `hip_stream` before the call returns,
- *    so callers see ordinary single-stream semantics.
+ *    per-micro-batch weight-gradient products, the bias / gain reductions)
+ *    on a stream of its own (created on the first call, at the default
+ *    priority); it is ordered after the work it consumes and joined back into
+ *    `hip_stream` before the call returns, so callers see ordinary
+ *    single-stream semantics.
  *  - Matrices are row-major.  Rows of an activation are ordered batch-major:
  *    row = b * seq_len + s.  Linear layers are y = x W + b with W[in, out].
  *  - Activations and parameters are bf16 (bit pattern in uint16_t), gradients

@@ -21,6 +21,7 @@
 // mask both walk every tile of the sequence).
 #include "common.h"
 #include "kernels.h"
+#include <cstdlib>
 
 namespace ah {
 namespace {
@@ -271,6 +272,160 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict
   if (hf == 0) lse[((size_t)b * nh + head) * S + q] = (st.m + __log2f(l)) * LN2;
 }
 
+// =========================================================================== forward for launches that cannot fill the chip
+// With at most one 128-query block per CU a wave sits alone on its SIMD and the launch lasts as long as the block
+// with the most key tiles.  Here a block takes 64 queries and its four waves split the work two ways: wave w
+// owns queries 32 * (w & 1) .. + 31 and, of every 64-key tile, the keys 32 * (w >> 1) .. + 31.  There are twice as
+// many blocks (two per CU, heavy ones paired with light ones) and every wave walks half the keys of its queries;
+// the two partial results per query (running maximum, sum and output accumulator) meet in LDS at the end.
+template <int D>
+__device__ __forceinline__ void fwd_half_tile(const char* __restrict__ cK, const char* __restrict__ cV, FwdState<D>& st, int kbase,
+                                              int kh, int q, bool diag, float sc2, int lane) {
+  constexpr int NK = D / 16, ND = D / 32;
+  const int hf = lane >> 5;
+  bf16x8 fk[NK];
+#pragma unroll
+  for (int ks = 0; ks < NK; ks++) fk[ks] = frag_rowmajor<D>(cK, 32 * kh + (lane & 31), ks, hf);
+  AH_SCHED_FENCE();
+  f32x16 s;
+#pragma unroll
+  for (int r = 0; r < 16; r++) s[r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < NK; ks++) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[ks], st.qf[ks], s, 0, 0, 0);
+  bf16x8 v[2][ND];
+#pragma unroll
+  for (int s2 = 0; s2 < 2; s2++)
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++) v[s2][dt] = frag_transposed<D>(cV, 32 * kh + 16 * s2 + 4 * hf, dt, lane);
+  AH_SCHED_FENCE();
+  if (diag) {
+    // element r is key kbase + 8*(r/4) + 4*hf + r%4: masked iff that exceeds q
+    const int lim = q - kbase - 4 * hf;
+#pragma unroll
+    for (int r = 0; r < 16; r++)
+      if (8 * (r >> 2) + (r & 3) > lim) s[r] = -INFINITY;
+  }
+  float mx = s[0];
+#pragma unroll
+  for (int r = 1; r < 16; r++) mx = fmaxf(mx, s[r]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc2;
+  if (__any(mx > st.m + RESCALE_SLACK)) {  // wave-uniform branch
+    const float m_new = fmaxf(st.m, mx);
+    const float alpha = fexp2(st.m - m_new);
+    st.m = m_new;
+    st.l *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) st.oacc[dt][r] *= alpha;
+  }
+  const float nm = -st.m;
+  float ls = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    s[r] = fexp2(__builtin_fmaf(s[r], sc2, nm));
+    ls += s[r];
+  }
+  st.l += ls;
+  AH_SCHED_FENCE();
+#pragma unroll
+  for (int s2 = 0; s2 < 2; s2++) {
+    const bf16x8 pf = pack8(s, s2);
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++) st.oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[s2][dt], pf, st.oacc[dt], 0, 0, 0);
+  }
+  AH_SCHED_FENCE();
+}
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void attn_fwd64_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
+                                                         int S, int nh, float sc2) {
+  constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, LPS = 2 * (D / 32), ND = D / 32;
+  __shared__ __attribute__((aligned(1024))) char ring[NSLOT * STAGE];
+  static_assert(2 * (ND * 16 + 2) * 64 * 4 <= NSLOT * STAGE, "the partial results of two waves fit in the ring");
+  const int lane = threadIdx.x & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qt = wave & 1, kh = wave >> 1;
+  const int nq = S / 64;
+  const int nbh = gridDim.x / nq;
+  const int bh = blockIdx.x % nbh;
+  const int qb = CAUSAL ? causal_query_block(blockIdx.x / nbh, nq) : blockIdx.x / nbh;
+  const int b = bh / nh, head = bh % nh;
+  const int ld = 3 * nh * D;
+  const bf16* qp = qkv + (size_t)b * S * ld + head * D;
+  const bf16* kp = qp + nh * D;
+  const bf16* vp = qp + 2 * nh * D;
+  const int qw0 = qb * 64 + qt * 32, q = qw0 + (lane & 31);
+
+  FwdState<D> st;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ks++) st.qf[ks] = *(const bf16x8*)(qp + (size_t)q * ld + ks * 16 + hf * 8);
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) st.oacc[dt][r] = 0.f;
+  st.m = -INFINITY;
+  st.l = 0.f;
+
+  uint32_t off[D / 32];
+#pragma unroll
+  for (int i = 0; i < D / 32; i++) off[i] = tile_src_offset<D>(wave + 4 * i, lane, ld);
+
+  // key tiles of 64 up to and including the one that holds the block's own keys; tile t lives in ring slot t % 2
+  // and is fetched during step t - 1 (past the end the last tile again, into a slot nobody reads)
+  const int ntile = CAUSAL ? qb + 1 : nq, last = ntile - 1;
+  const size_t step = (size_t)64 * ld;
+  issue_tile<D>(kp, off, ring, wave);
+  issue_tile<D>(vp, off, ring + TILEB, wave);
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+  __builtin_amdgcn_s_barrier();
+  for (int j = 0; j < ntile; j++) {
+    const size_t o2 = (size_t)min(j + 1, last) * step;
+    char* fill = ring + ((j + 1) & 1) * STAGE;
+    const char* cur = ring + (j & 1) * STAGE;
+    issue_tile<D>(kp + o2, off, fill, wave);
+    issue_tile<D>(vp + o2, off, fill + TILEB, wave);
+    // In the block's own tile the wave's keys lie before (kh < qt), on (kh == qt) or after (kh > qt) its queries.
+    const bool own = CAUSAL && j == last;
+    if (!(own && kh > qt)) fwd_half_tile<D>(cur, cur + TILEB, st, j * 64 + 32 * kh, kh, q, own && kh == qt, sc2, lane);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+    __builtin_amdgcn_s_barrier();
+  }
+
+  // merge: the waves of the second key half leave (m, l, O) in LDS, lane by lane; the others fold them in
+  float* mg = (float*)ring + (size_t)qt * (ND * 16 + 2) * 64;
+  if (kh == 1) {
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) mg[(dt * 16 + r) * 64 + lane] = st.oacc[dt][r];
+    mg[(ND * 16) * 64 + lane] = st.m;
+    mg[(ND * 16 + 1) * 64 + lane] = st.l;
+  }
+  __syncthreads();
+  if (kh == 1) return;
+  const float m2 = mg[(ND * 16) * 64 + lane], l2 = mg[(ND * 16 + 1) * 64 + lane];
+  const float m = fmaxf(st.m, m2);
+  const float a1 = fexp2(st.m - m), a2 = fexp2(m2 - m);  // m2 = -inf (nothing visible in that half) gives a2 = 0
+  const float lsum = a1 * st.l + a2 * l2;
+  const float l = lsum + __shfl_xor(lsum, 32, 64);
+  const float inv = 1.f / l;
+  bf16* op = o + ((size_t)b * S + q) * (nh * D) + head * D;
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      bf16x4 v;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int r = 4 * g + i;
+        v[i] = f2bf((a1 * st.oacc[dt][r] + a2 * mg[(dt * 16 + r) * 64 + lane]) * inv);
+      }
+      *(bf16x4*)(op + dt * 32 + 8 * g + 4 * hf) = v;
+    }
+  if (hf == 0) lse[((size_t)b * nh + head) * S + q] = (m + __log2f(l)) * LN2;
+}
+
 // =========================================================================== backward: delta = rowsum(dO * O)
 template <int D>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16* __restrict__ o, const bf16* __restrict__ d_o,
@@ -460,6 +615,154 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict_
       bf16x4 v;
 #pragma unroll
       for (int i = 0; i < 4; i++) v[i] = f2bf(st.acc[dt][4 * g + i] * scale);
+      *(bf16x4*)(out + dt * 32 + 8 * g + 4 * hf) = v;
+    }
+}
+
+// =========================================================================== backward: dQ for launches that cannot fill the chip
+// The split of attn_fwd64_kernel applied to dQ: 64 queries per block, wave w owns queries 32 * (w & 1) .. + 31 and
+// keys 32 * (w >> 1) .. + 31 of every 64-key tile; the two partial dQ per query are added in LDS at the end.
+template <int D>
+__device__ __forceinline__ void dq_half_tile(const char* __restrict__ cK, const char* __restrict__ cV, DqState<D>& st, int kbase,
+                                             int kh, int q, bool diag, float sc2, int lane) {
+  constexpr int NK = D / 16, ND = D / 32;
+  const int hf = lane >> 5;
+  // with head_dim 128 the 256 registers of a wave (two blocks share a CU) leave no room for all fragments at once:
+  // they are fetched where they are used and the other block covers the wait
+  constexpr bool AHEAD = D == 64;
+  bf16x8 fk[NK], fv[NK];
+  if (AHEAD) {
+#pragma unroll
+    for (int ks = 0; ks < NK; ks++) {
+      fk[ks] = frag_rowmajor<D>(cK, 32 * kh + (lane & 31), ks, hf);
+      fv[ks] = frag_rowmajor<D>(cV, 32 * kh + (lane & 31), ks, hf);
+    }
+    AH_SCHED_FENCE();
+  }
+  f32x16 s, dp;
+#pragma unroll
+  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+  for (int ks = 0; ks < NK; ks++) {
+    if (!AHEAD) {
+      fk[ks] = frag_rowmajor<D>(cK, 32 * kh + (lane & 31), ks, hf);
+      fv[ks] = frag_rowmajor<D>(cV, 32 * kh + (lane & 31), ks, hf);
+    }
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[ks], st.qf[ks], s, 0, 0, 0);
+    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[ks], st.dof[ks], dp, 0, 0, 0);
+  }
+  bf16x8 kt[2][ND];
+  if (AHEAD) {
+#pragma unroll
+    for (int s2 = 0; s2 < 2; s2++)
+#pragma unroll
+      for (int dt = 0; dt < ND; dt++) kt[s2][dt] = frag_transposed<D>(cK, 32 * kh + 16 * s2 + 4 * hf, dt, lane);
+    AH_SCHED_FENCE();
+  }
+  const float nl = -st.lse2;
+#pragma unroll
+  for (int r = 0; r < 16; r++) {
+    s[r] = fexp2(__builtin_fmaf(s[r], sc2, nl));
+    dp[r] -= st.delta;
+  }
+  if (diag) {  // wave-uniform; element r is key kbase + 8*(r/4) + 4*hf + r%4
+    const int lim = q - kbase - 4 * hf;
+#pragma unroll
+    for (int r = 0; r < 16; r++)
+      if (8 * (r >> 2) + (r & 3) > lim) s[r] = 0.f;
+  }
+#pragma unroll
+  for (int r = 0; r < 16; r++) s[r] *= dp[r];  // dS^T
+  if (AHEAD) AH_SCHED_FENCE();
+#pragma unroll
+  for (int s2 = 0; s2 < 2; s2++) {
+    const bf16x8 dsf = pack8(s, s2);
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++) {
+      if (!AHEAD) kt[s2][dt] = frag_transposed<D>(cK, 32 * kh + 16 * s2 + 4 * hf, dt, lane);
+      st.acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[s2][dt], dsf, st.acc[dt], 0, 0, 0);
+    }
+  }
+  if (AHEAD) AH_SCHED_FENCE();
+}
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void attn_dq64_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
+                                                        const float* __restrict__ lse, const float* __restrict__ delta,
+                                                        bf16* __restrict__ dqkv, int S, int nh, float sc2, float scale) {
+  constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, ND = D / 32;
+  __shared__ __attribute__((aligned(1024))) char ring[NSLOT * STAGE];
+  static_assert(2 * ND * 16 * 64 * 4 <= NSLOT * STAGE, "the partial results of two waves fit in the ring");
+  const int lane = threadIdx.x & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qt = wave & 1, kh = wave >> 1;
+  const int nq = S / 64;
+  const int nbh = gridDim.x / nq;
+  const int bh = blockIdx.x % nbh;
+  const int qb = CAUSAL ? causal_query_block(blockIdx.x / nbh, nq) : blockIdx.x / nbh;
+  const int b = bh / nh, head = bh % nh;
+  const int ld = 3 * nh * D;
+  const bf16* qp = qkv + (size_t)b * S * ld + head * D;
+  const bf16* kp = qp + nh * D;
+  const bf16* vp = qp + 2 * nh * D;
+  const int qw0 = qb * 64 + qt * 32, q = qw0 + (lane & 31);
+
+  DqState<D> st;
+  const bf16* dop = d_o + ((size_t)b * S + q) * (nh * D) + head * D;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ks++) {
+    st.qf[ks] = *(const bf16x8*)(qp + (size_t)q * ld + ks * 16 + hf * 8);
+    st.dof[ks] = *(const bf16x8*)(dop + ks * 16 + hf * 8);
+  }
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) st.acc[dt][r] = 0.f;
+  st.lse2 = lse[((size_t)b * nh + head) * S + q] * LOG2E;
+  st.delta = delta[((size_t)b * nh + head) * S + q];
+
+  uint32_t off[D / 32];
+#pragma unroll
+  for (int i = 0; i < D / 32; i++) off[i] = tile_src_offset<D>(wave + 4 * i, lane, ld);
+
+  const int ntile = CAUSAL ? qb + 1 : nq, last = ntile - 1;
+  const size_t step = (size_t)64 * ld;
+  issue_tile<D>(kp, off, ring, wave);
+  issue_tile<D>(vp, off, ring + TILEB, wave);
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+  __builtin_amdgcn_s_barrier();
+  for (int j = 0; j < ntile; j++) {
+    const size_t o2 = (size_t)min(j + 1, last) * step;
+    char* fill = ring + ((j + 1) & 1) * STAGE;
+    const char* cur = ring + (j & 1) * STAGE;
+    issue_tile<D>(kp + o2, off, fill, wave);
+    issue_tile<D>(vp + o2, off, fill + TILEB, wave);
+    const bool own = CAUSAL && j == last;
+    if (!(own && kh > qt)) dq_half_tile<D>(cur, cur + TILEB, st, j * 64 + 32 * kh, kh, q, own && kh == qt, sc2, lane);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
+    __builtin_amdgcn_s_barrier();
+  }
+
+  float* mg = (float*)ring + (size_t)qt * ND * 16 * 64;
+  if (kh == 1) {
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) mg[(dt * 16 + r) * 64 + lane] = st.acc[dt][r];
+  }
+  __syncthreads();
+  if (kh == 1) return;
+  bf16* out = dqkv + ((size_t)b * S + q) * ld + head * D;
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      bf16x4 v;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int r = 4 * g + i;
+        v[i] = f2bf((st.acc[dt][r] + mg[(dt * 16 + r) * 64 + lane]) * scale);
+      }
       *(bf16x4*)(out + dt * 32 + 8 * g + 4 * hf) = v;
     }
 }
@@ -670,13 +973,202 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(const bf16* __restrict__ 
     }
 }
 
+// =========================================================================== backward: dK, dV for launches that cannot fill the chip
+// 64 keys per block instead of 128 (twice the blocks, dispatched heaviest first, so that the CUs even out): wave w
+// owns keys 32 * (w & 1) .. + 31 of the block and, of every 64-query tile, the queries 32 * (w >> 1) .. + 31; the two
+// partial dK, dV per key are added in LDS at the end.
+template <int D>
+__device__ __forceinline__ void dkv_half_tile(const char* __restrict__ cQ, const char* __restrict__ cO, DkvState<D>& st,
+                                              const float* __restrict__ lse_tile, const float* __restrict__ delta_tile, int q0, int key,
+                                              int t, bool diag, float sc2, int lane) {
+  constexpr int NK = D / 16, ND = D / 32;
+  const int hf = lane >> 5;
+  const int lim = key - q0 - 4 * hf;  // query offset ql (without the 4*hf term) is masked iff ql < lim
+  bf16x8 fq[NK], fo[NK];
+#pragma unroll
+  for (int ks = 0; ks < NK; ks++) {
+    fq[ks] = frag_rowmajor<D>(cQ, 32 * t + (lane & 31), ks, hf);
+    fo[ks] = frag_rowmajor<D>(cO, 32 * t + (lane & 31), ks, hf);
+  }
+  AH_SCHED_FENCE();
+  f32x16 s, dp;
+#pragma unroll
+  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+  bf16x8 tq0[ND], to0[ND], tq1[ND], to1[ND];
+#pragma unroll
+  for (int ks = 0; ks < NK; ks++) {
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[ks], st.kf[ks], s, 0, 0, 0);
+    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[ks], st.vf[ks], dp, 0, 0, 0);
+  }
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++) {
+    to0[dt] = frag_transposed<D>(cO, t * 32 + 4 * hf, dt, lane);
+    tq0[dt] = frag_transposed<D>(cQ, t * 32 + 4 * hf, dt, lane);
+  }
+  AH_SCHED_FENCE();
+  // lane holds queries q0 + t*32 + 8g + 4hf + i of its key
+#pragma unroll
+  for (int g = 0; g < 4; g++) {
+    const int ql = t * 32 + 8 * g + 4 * hf;
+    const f32x4 l4 = *(const f32x4*)(lse_tile + ql);
+    const f32x4 d4 = *(const f32x4*)(delta_tile + ql);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int r = 4 * g + i;
+      s[r] = fexp2(__builtin_fmaf(s[r], sc2, -l4[i] * LOG2E));
+      dp[r] -= d4[i];
+    }
+  }
+  if (diag) {  // wave-uniform
+#pragma unroll
+    for (int r = 0; r < 16; r++)
+      if (t * 32 + 8 * (r >> 2) + (r & 3) < lim) s[r] = 0.f;
+  }
+#pragma unroll
+  for (int r = 0; r < 16; r++) dp[r] *= s[r];
+  AH_SCHED_FENCE();
+  const bf16x8 pf0 = pack8(s, 0), dsf0 = pack8(dp, 0), pf1 = pack8(s, 1), dsf1 = pack8(dp, 1);
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++) {
+    to1[dt] = frag_transposed<D>(cO, t * 32 + 16 + 4 * hf, dt, lane);
+    tq1[dt] = frag_transposed<D>(cQ, t * 32 + 16 + 4 * hf, dt, lane);
+  }
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++) {
+    st.dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to0[dt], pf0, st.dv[dt], 0, 0, 0);
+    st.dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq0[dt], dsf0, st.dk[dt], 0, 0, 0);
+  }
+  AH_SCHED_FENCE();
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++) {
+    st.dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to1[dt], pf1, st.dv[dt], 0, 0, 0);
+    st.dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq1[dt], dsf1, st.dk[dt], 0, 0, 0);
+  }
+  AH_SCHED_FENCE();
+}
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_dkv64_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
+                                                         const float* __restrict__ lse, const float* __restrict__ delta,
+                                                         bf16* __restrict__ dqkv, int S, int nh, float sc2, float scale) {
+  constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB + 1024, LPS = 2 * (D / 32) + 1, ND = D / 32;
+  __shared__ __attribute__((aligned(1024))) char ring[4 * STAGE];
+  static_assert(2 * 2 * ND * 16 * 64 * 4 <= 4 * STAGE, "the partial results of two waves fit in the ring");
+  const int lane = threadIdx.x & 63, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int kt = wave & 1, qh = wave >> 1;
+  const int nkb = S / 64;
+  const int nbh = gridDim.x / nkb;
+  const int bh = blockIdx.x % nbh;
+  const int kb = blockIdx.x / nbh;  // key block 0 sees every query tile: heaviest first
+  const int b = bh / nh, head = bh % nh;
+  const int ld = 3 * nh * D, ldo = nh * D;
+  const bf16* qp = qkv + (size_t)b * S * ld + head * D;
+  const bf16* kp = qp + nh * D;
+  const bf16* vp = qp + 2 * nh * D;
+  const bf16* dop = d_o + (size_t)b * S * ldo + head * D;
+  const int kw0 = kb * 64 + kt * 32, key = kw0 + (lane & 31);
+  const float* lse_row = lse + ((size_t)b * nh + head) * S;
+  const float* delta_row = delta + ((size_t)b * nh + head) * S;
+
+  DkvState<D> st;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ks++) {
+    st.kf[ks] = *(const bf16x8*)(kp + (size_t)key * ld + ks * 16 + hf * 8);
+    st.vf[ks] = *(const bf16x8*)(vp + (size_t)key * ld + ks * 16 + hf * 8);
+  }
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) { st.dk[dt][r] = 0.f; st.dv[dt][r] = 0.f; }
+
+  uint32_t offq[D / 32], offo[D / 32];
+#pragma unroll
+  for (int i = 0; i < D / 32; i++) {
+    offq[i] = tile_src_offset<D>(wave + 4 * i, lane, ld);
+    offo[i] = tile_src_offset<D>(wave + 4 * i, lane, ldo);
+  }
+
+  // query tiles of 64 from the one that holds the block's own positions on (from 0 without the mask); ring and
+  // counted waits as in attn_dkv_kernel
+  const int j0 = CAUSAL ? kb : 0, ntile = S / 64 - j0, last = ntile - 1;
+  qp += (size_t)j0 * 64 * ld;
+  dop += (size_t)j0 * 64 * ldo;
+  lse_row += j0 * 64;
+  delta_row += j0 * 64;
+  const size_t stepq = (size_t)64 * ld, stepo = (size_t)64 * ldo;
+#pragma unroll
+  for (int t = 0; t < 3; t++) {
+    const int tt = min(t, last);
+    dkv_issue<D>(qp + tt * stepq, dop + tt * stepo, lse_row + tt * 64, delta_row + tt * 64, offq, offo, ring + t * STAGE, wave, lane);
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+  __builtin_amdgcn_s_barrier();
+  for (int j = 0; j < ntile; j++) {
+    const int tf = min(j + 3, last);
+    dkv_issue<D>(qp + tf * stepq, dop + tf * stepo, lse_row + tf * 64, delta_row + tf * 64, offq, offo, ring + ((j + 3) & 3) * STAGE, wave,
+                 lane);
+    const char* cur = ring + (j & 3) * STAGE;
+    const float* lse_tile = (const float*)(cur + 2 * TILEB);
+    // in the block's own tile the wave's queries lie before (qh < kt), on (qh == kt) or after (qh > kt) its keys
+    const bool own = CAUSAL && j == 0;
+    if (!(own && qh < kt))
+      dkv_half_tile<D>(cur, cur + TILEB, st, lse_tile, lse_tile + 64, (j0 + j) * 64, key, qh, own && qh == kt, sc2, lane);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
+    __builtin_amdgcn_s_barrier();
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));  // drain the redundant tail loads
+  __syncthreads();
+
+  float* mg = (float*)ring + (size_t)kt * 2 * ND * 16 * 64;
+  if (qh == 1) {
+#pragma unroll
+    for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        mg[(dt * 16 + r) * 64 + lane] = st.dk[dt][r];
+        mg[((ND + dt) * 16 + r) * 64 + lane] = st.dv[dt][r];
+      }
+  }
+  __syncthreads();
+  if (qh == 1) return;
+  bf16* outk = dqkv + ((size_t)b * S + key) * ld + nh * D + head * D;
+  bf16* outv = outk + nh * D;
+#pragma unroll
+  for (int dt = 0; dt < ND; dt++)
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      bf16x4 a, c;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int r = 4 * g + i;
+        a[i] = f2bf((st.dk[dt][r] + mg[(dt * 16 + r) * 64 + lane]) * scale);
+        c[i] = f2bf(st.dv[dt][r] + mg[((ND + dt) * 16 + r) * 64 + lane]);
+      }
+      *(bf16x4*)(outk + dt * 32 + 8 * g + 4 * hf) = a;
+      *(bf16x4*)(outv + dt * 32 + 8 * g + 4 * hf) = c;
+    }
+}
+
 }  // namespace
+
+// Launches of at most this many 128-row blocks (one per CU) take the 64-row kernels, which split every block's work
+// between wave pairs: twice the blocks, so that the CUs even out under the causal mask and a SIMD has two waves
+// (gpt1p3b stage, 1 x 16 heads x 2048: forward 48 -> 36 us, backward 144 -> 114 us); larger launches fill the chip
+// with 128-row blocks and are 8 % faster with them.
+static int small_grid_blocks() {
+  static const int v = getenv("AH_ATTN_SMALL_GRID") ? atoi(getenv("AH_ATTN_SMALL_GRID")) : 256;  // tuning aid
+  return v;
+}
 
 static bool attn_shape_ok(int B, int S, int nh, int d) { return B > 0 && nh > 0 && S > 0 && S % 128 == 0 && (d == 64 || d == 128); }
 
 template <int D, bool CAUSAL>
 static void launch_fwd_t(dim3 grid, hipStream_t s, const void* qkv, void* o, float* lse, int S, int nh, float sc2) {
-  hipLaunchKernelGGL((attn_fwd_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, S, nh, sc2);
+  if ((int)grid.x <= small_grid_blocks())  // at most one 128-query block per CU: 64-query blocks with the keys split between wave pairs
+    hipLaunchKernelGGL((attn_fwd64_kernel<D, CAUSAL>), dim3(2 * grid.x), dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, S, nh, sc2);
+  else
+    hipLaunchKernelGGL((attn_fwd_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, S, nh, sc2);
 }
 
 hipError_t launch_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, bool causal, hipStream_t s) {
@@ -694,52 +1186,39 @@ hipError_t launch_attention_fwd(const void* qkv, void* o, float* lse, int B, int
 }
 
 template <int D, bool CAUSAL>
-static hipError_t launch_bwd_t(dim3 grid, dim3 dgrid, hipStream_t s, const AttnBwdFork* fk, const void* qkv, const void* o, const float* lse,
-                               const void* d_o, void* dqkv, float* delta, int T, int S, int nh, float sc2, float scale) {
+static void launch_bwd_t(dim3 grid, dim3 dgrid, hipStream_t s, const void* qkv, const void* o, const float* lse, const void* d_o,
+                         void* dqkv, float* delta, int T, int S, int nh, float sc2, float scale) {
   hipLaunchKernelGGL(attn_delta_kernel<D>, dgrid, dim3(256), 0, s, (const bf16*)o, (const bf16*)d_o, delta, T, S, nh);
-  // The dK/dV kernel and the dQ kernel both need delta and write disjoint column blocks of dqkv: given a second
-  // stream they run side by side, and the blocks of one fill the CUs that the uneven (causal) blocks of the other
-  // leave idle.
-  hipStream_t sq = s;
-  if (fk) {
-    hipError_t e = hipEventRecord(fk->fork, s);
-    if (e == hipSuccess) e = hipStreamWaitEvent(fk->stream, fk->fork, 0);
-    if (e != hipSuccess) return e;
-    sq = fk->stream;
-  }
-  hipLaunchKernelGGL((attn_dkv_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv,
-                     S, nh, sc2, scale);
-  hipLaunchKernelGGL((attn_dq_kernel<D, CAUSAL>), grid, dim3(256), 0, sq, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv,
-                     S, nh, sc2, scale);
-  if (fk) {
-    hipError_t e = hipEventRecord(fk->join, fk->stream);
-    if (e == hipSuccess) e = hipStreamWaitEvent(s, fk->join, 0);
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
+  if ((int)grid.x <= small_grid_blocks())  // at most one 128-key block per CU: 64-key blocks with the queries split between wave pairs
+    hipLaunchKernelGGL((attn_dkv64_kernel<D, CAUSAL>), dim3(2 * grid.x), dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta,
+                       (bf16*)dqkv, S, nh, sc2, scale);
+  else
+    hipLaunchKernelGGL((attn_dkv_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv,
+                       S, nh, sc2, scale);
+  if ((int)grid.x <= small_grid_blocks())  // at most one 128-query block per CU: 64-query blocks with the keys split between wave pairs
+    hipLaunchKernelGGL((attn_dq64_kernel<D, CAUSAL>), dim3(2 * grid.x), dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta,
+                       (bf16*)dqkv, S, nh, sc2, scale);
+  else
+    hipLaunchKernelGGL((attn_dq_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv,
+                       S, nh, sc2, scale);
 }
 
 hipError_t launch_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
-                                int B, int S, int nh, int d, bool causal, hipStream_t s, const AttnBwdFork* fk) {
+                                int B, int S, int nh, int d, bool causal, hipStream_t s) {
   if (!attn_shape_ok(B, S, nh, d)) return hipErrorInvalidValue;
-  // Side by side pays when one kernel alone cannot fill the chip: at most one dK/dV block per CU, whose lengths
-  // differ under the causal mask (gpt1p3b stage: 31.1 -> 29.8 ms per step).  With more blocks than CUs each kernel
-  // fills the chip by itself and the two only get in each other's way (gpt7b_tp2 stage: 81.0 -> 83.0 ms).
-  if (fk && (fk->stream == s || (long)B * nh * (S / 128) > 256)) fk = nullptr;
-  hipError_t e;
   const float scale = 1.f / sqrtf((float)d), sc2 = LOG2E * scale;
   const int T = B * S;
   const dim3 grid(B * nh * (S / 128));
   const long nthreads = (long)T * nh * (d / 8);
   const dim3 dgrid((unsigned)((nthreads + 255) / 256));
   if (d == 128) {
-    if (causal) e = launch_bwd_t<128, true>(grid, dgrid, s, fk, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
-    else e = launch_bwd_t<128, false>(grid, dgrid, s, fk, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
+    if (causal) launch_bwd_t<128, true>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
+    else launch_bwd_t<128, false>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
   } else {
-    if (causal) e = launch_bwd_t<64, true>(grid, dgrid, s, fk, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
-    else e = launch_bwd_t<64, false>(grid, dgrid, s, fk, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
+    if (causal) launch_bwd_t<64, true>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
+    else launch_bwd_t<64, false>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
   }
-  return e != hipSuccess ? e : hipGetLastError();
+  return hipGetLastError();
 }
 
 }  // namespace ah

@@ -48,11 +48,8 @@ bool gemm_segments_ok(int seg_k, int n_seg);  // seg_k a positive multiple of 12
 // ---- attention (d = 64 or 128, S multiple of 128) ----
 // causal: query i attends to keys 0..i of its sequence; otherwise to all S keys
 hipError_t launch_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh, int d, bool causal, hipStream_t s);
-// fork (optional): a second stream and two events of the caller's; the dQ kernel then runs on that stream beside the
-// dK/dV kernel, ordered after delta by `fork` and joined back into s by `join` before the call returns
-struct AttnBwdFork { hipStream_t stream; hipEvent_t fork, join; };
 hipError_t launch_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
-                                float* delta, int B, int S, int nh, int d, bool causal, hipStream_t s, const AttnBwdFork* fork = nullptr);
+                                float* delta, int B, int S, int nh, int d, bool causal, hipStream_t s);
 
 // ---- row-wise / element-wise kernels (bf16 I/O, fp32 math) ----
 // a = norm(x) * gamma (+ beta); stats[2*T] = (mean, rstd) per row (RMS: mean slot unused = 0)

@@ -67,8 +67,8 @@ struct ah_stage {
   bool tracing;
   // Second stream for the work of backward that nothing downstream waits for (weight gradients, column-sum
   // reductions); created on first use, joined back into the caller's stream before every return.
-  hipStream_t side, side2;  // side2: the dQ kernel of attention backward, beside the dK/dV kernel
-  hipEvent_t sync_ev[10];
+  hipStream_t side;
+  hipEvent_t sync_ev[8];
   bool side_ready, side_off;
   std::vector<hipEvent_t> ev_pool;           // pairs, in launch order
   std::vector<int> ev_site;                  // site of pair i
@@ -435,9 +435,9 @@ hipError_t stream_order(hipStream_t from, hipStream_t to, hipEvent_t ev) {
 // waits for the side stream before a buffer the side stream still reads is rewritten (du, by attention backward,
 // where dqkv shares its buffer) and at the end of the layer (workspace and, with recompute, the shared activation
 // working set are reused by the next layer).  bb: where the intermediate gradients go; wp, vp: what happens to
-// the matrix and vector gradients now (see WgradPlan, VecPlan); fork_ok: attention backward may use side2.
+// the matrix and vector gradients now (see WgradPlan, VecPlan).
 hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* dy, void* dx, const VecPlan& vp, const BwdBufs& bb,
-                          const WgradPlan& wp, hipStream_t st, hipStream_t sd, bool fork_ok) {
+                          const WgradPlan& wp, hipStream_t st, hipStream_t sd) {
   const LayerPtrs p = layer_ptrs(s, layer);
   const int T = s->T, h = s->h, hl = s->hl, F = s->F, B = s->cfg.microbatch_size, S = s->cfg.seq_len;
   const int Fu = s->llama ? 2 * F : F;
@@ -485,8 +485,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
   // attention (where dqkv shares its buffer with du: wait until the first MLP matrix's weight gradient has read it)
   if (sd != st && dqkv == du) TRY(hipStreamWaitEvent(st, ev[2], 0));
-  const AttnBwdFork fk = {s->side2, ev[7], ev[8]};
-  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dqkv, delta, B, S, s->nh, s->d, s->causal, st, fork_ok ? &fk : nullptr));
+  TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dqkv, delta, B, S, s->nh, s->d, s->causal, st));
   if (s->llama) TIMED(SITE_ROPE, launch_rope(dqkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
   TRY(stream_order(st, sd, ev[4]));
   if (!s->llama) {
@@ -513,8 +512,6 @@ hipError_t ensure_side(ah_stage* s) {
   if (s->side_ready || s->side_off) return hipSuccess;
   if (getenv("AH_NO_SIDE_STREAM")) { s->side_off = true; return hipSuccess; }
   hipError_t e = hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking);
-  if (e != hipSuccess) return e;
-  e = hipStreamCreateWithFlags(&s->side2, hipStreamNonBlocking);
   if (e != hipSuccess) return e;
   for (auto& v : s->sync_ev) {
     e = hipEventCreateWithFlags(&v, hipEventDisableTiming);
@@ -633,7 +630,7 @@ hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipSt
       }
     }
     const VecPlan vp = vec_plan(s, l, deferred, pos, closes_group, beta, wp.beta);
-    TRY(layer_backward(s, l, a, cur, out, vp, bb, wp, st, sd, streams_ok));
+    TRY(layer_backward(s, l, a, cur, out, vp, bb, wp, st, sd));
     cur = out;
     if (ev) TRY(hipEventRecord(ev[l], st));
   }
@@ -694,7 +691,6 @@ extern "C" int ah_stage_create(const ah_stage_config_t* cfg, const ah_stage_buff
   s->force_immediate = false;
   s->rope_ready = false;
   s->side = nullptr;
-  s->side2 = nullptr;
   s->side_ready = false;
   s->side_off = false;
   s->tracing = false;
@@ -708,8 +704,6 @@ extern "C" int ah_stage_destroy(ah_stage_t* st) {
     for (hipEvent_t e : st->ev_pool) (void)hipEventDestroy(e);
     if (st->side_ready) {
       (void)hipStreamSynchronize(st->side);
-      (void)hipStreamSynchronize(st->side2);
-      (void)hipStreamDestroy(st->side2);
       for (hipEvent_t e : st->sync_ev) (void)hipEventDestroy(e);
       (void)hipStreamDestroy(st->side);
     }

@@ -70,7 +70,9 @@ def test_gemm_at_benchmark_shapes_sampled_entries(layout, M, N, K):
 
 
 @pytest.mark.parametrize("B,S,nh,d,causal", [(2, 2048, 16, 128, True), (1, 4096, 32, 128, True), (8, 512, 16, 64, False),
-                                              (1, 2048, 4, 128, False)])
+                                              (1, 2048, 4, 128, False),
+                                              # launches of at most 256 blocks of 128 queries take the 64-query kernels
+                                              (1, 2048, 16, 128, True), (2, 1024, 4, 64, True), (1, 128, 2, 64, True)])
 def test_attention_at_benchmark_shapes_sampled_heads(B, S, nh, d, causal):
     rng = np.random.default_rng(8)
     T, hl = B * S, nh * d
