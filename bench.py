@@ -79,6 +79,7 @@ def main():
     ap.add_argument("--workload", default="gpt7b_tp2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--trace-steps", type=int, default=2)
+    ap.add_argument("--no-ungrouped", action="store_true", help="skip the comparison run with wgrad_group 1")
     ap.add_argument("--no-side-stream", action="store_true",
                     help="keep all of backward on one stream, as the per-site trace does: kernel durations in a profile are then "
                          "those of kernels that own the chip (the timed figure is ~1 %% lower)")
@@ -168,15 +169,67 @@ def main():
     dom = max(groups.values(), key=lambda g: g["total_ms"])
     avg_ms = dom["total_ms"] / dom["launches"]
     achieved = dom["flops_per_launch"] / (avg_ms * 1e-3) / 1e12
-    traffic = None
+    # HBM-side traffic of that kernel comes from hardware counters, which a plain run cannot read: it is taken from the
+    # committed rocprofv3 counter summary, and only if that summary was made with this very GEMM source and launch
+    # shape (it records the hash of csrc/gemm.hip); otherwise null.
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.md" % args.workload)
-    if os.path.exists(tpath) and any(n.startswith("gemm_tn.fc") for n in dom["names"]):
-        meta = dict(l.split(":", 1) for l in open(tpath) if l.startswith(("traffic_bytes_per_launch:", "wgrad_group:")))
-        if int(meta.get("wgrad_group", -1)) == G:   # the counter runs cover this launch shape only
-            traffic = float(meta["traffic_bytes_per_launch"])   # fetch + write bytes of this kernel from the rocprofv3 counter runs
-    roofline = {"bound": "mfma", "kernel": "+".join(dom["names"]), "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "avg_launch_us": avg_ms * 1e3,
-                "launches": dom["launches"], "flops_per_launch": dom["flops_per_launch"]}
+    is_mlp_wgrad = any(n.startswith("gemm_tn.fc") for n in dom["names"])
+    if os.path.exists(tpath) and is_mlp_wgrad:
+        import hashlib
+        sha = hashlib.sha256(open(os.path.join(ROOT, "paper_2512_20953_amd", "csrc", "gemm.hip"), "rb").read()).hexdigest()[:16]
+        meta = dict(l.split(":", 1) for l in open(tpath) if l.startswith(("traffic_bytes_per_launch:", "wgrad_group:", "gemm_hip_sha256:")))
+        if int(meta.get("wgrad_group", -1)) == G and meta.get("gemm_hip_sha256", "").strip() == sha:
+            traffic = float(meta["traffic_bytes_per_launch"])
+            traffic_source = "profiles/hbm_traffic_%s.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, csrc/gemm.hip %s)" % (args.workload, sha)
+    # algorithmic bytes of one launch of the dominant kernel: each bf16 operand once, the fp32 result written once
+    algorithmic_bytes = None
+    if is_mlp_wgrad:
+        Tk, h_, F_ = T * G, w["hidden"], (2 if w["arch"] == "llama" else 1) * (w["ffn"] // w["tp"])
+        algorithmic_bytes = 2.0 * Tk * (h_ + F_) + 4.0 * h_ * F_ * (1 if G == K else 2)
+    roofline = {"bound": "mfma", "scope": "dominant kernel (largest total time in the step)", "kernel": "+".join(dom["names"]),
+                "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
+                "algorithmic_bytes": algorithmic_bytes, "avg_launch_us": avg_ms * 1e3,
+                "launches": dom["launches"], "flops_per_launch": dom["flops_per_launch"],
+                "whole_step_frac": tflops / PEAK_BF16_TFLOPS}
+
+    # the same step with per-micro-batch accumulation (wgrad_group 1: one activation slot instead of G), for comparison
+    ungrouped = None
+    if G > 1 and not args.no_ungrouped:
+        act_g = st.sizes["activation_bytes_per_slot"] * G + st.sizes["workspace_bytes"]
+        st.close()
+        del st
+        torch.cuda.empty_cache()
+        cfg1 = P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
+                                  head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
+                                  max_in_flight=1, recompute=w["recompute"], wgrad_group=1)
+        st1 = P.Stage(cfg1, device=dev)
+        st1.params.normal_(0.0, 0.02)
+        for l in range(w["n_layers"]):
+            for name in ("ln1_g", "ln2_g"):
+                st1.param_view(l, name).fill_(1.0)
+
+        def step1():
+            st1.zero_grads(stream)
+            for m in range(K):
+                st1.forward(0, xs[m], y, stream)
+                st1.backward(0, dys[m], dx, stream)
+
+        n1 = max(2, min(args.steps, 5))
+        for _ in range(2):
+            step1()
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(n1):
+            step1()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms1 = e0.elapsed_time(e1) / n1
+        ungrouped = {"wgrad_group": 1, "ms_per_step": ms1, "steps": n1, "tokens_per_s": tokens / (ms1 * 1e-3),
+                     "pct_of_bf16_mfma_peak": 100.0 * flops / (ms1 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "activation_and_workspace_bytes": st1.sizes["activation_bytes_per_slot"] + st1.sizes["workspace_bytes"],
+                     "activation_and_workspace_bytes_of_the_timed_configuration": act_g}
 
     out = {"metric": "stage fwd+bwd tokens/s and TFLOP/s (% bf16 MFMA peak) at 1 MI355X",
            "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -187,7 +240,7 @@ def main():
                       "local_heads": w["n_heads"] // w["tp"], "head_dim": w["head_dim"], "local_ffn": w["ffn"] // w["tp"],
                       "seq_len": w["seq"], "microbatch": w["mb"], "microbatches": K, "tokens_per_step": tokens,
                       "tp_degree": w["tp"], "recompute": w["recompute"], "wgrad_group": G, "parallelism": "1 GPU (one TP shard of one stage)"},
-           "roofline": roofline,
+           "roofline": roofline, "per_microbatch_accumulation": ungrouped,
            "sites": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in s.items()} for s in sites]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.workload)

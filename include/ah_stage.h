@@ -55,7 +55,8 @@ typedef enum {
   AH_ENOMEM = 2,       /* host allocation failed */
   AH_ESTATE = 3,       /* call order: forward on a busy slot, backward on an empty one */
   AH_EDEVICE = 4,      /* a HIP call failed */
-  AH_EUNSUPPORTED = 5  /* a shape the kernels do not cover (reported at create, never at launch) */
+  AH_EUNSUPPORTED = 5  /* a shape the kernels do not cover (reported at create, never at launch); also: ah_stage_backward /
+                        * ah_stage_flush_grads with wgrad_group > 1 on a stream that is being captured into a HIP graph */
 } ah_status_t;
 
 typedef enum {
@@ -79,14 +80,14 @@ typedef struct {
   uint32_t struct_size;     /* sizeof(ah_stage_config_t), checked */
   int32_t arch;             /* ah_arch_t */
   int32_t n_layers;         /* l_i: layers of this stage (Section III-C), >= 1 */
-  int32_t hidden;           /* h, multiple of 256, <= 16384 */
+  int32_t hidden;           /* h, multiple of 128, <= 16384 */
   int32_t n_heads;          /* heads of the unsharded layer */
   int32_t head_dim;         /* d: 64 or 128 */
   int32_t ffn_hidden;       /* FFN width of the unsharded layer */
   int32_t tp_degree;        /* must divide n_heads and ffn_hidden; local widths must be multiples of 128 */
   int32_t tp_rank;          /* 0 <= tp_rank < tp_degree (selects nothing inside the library: the caller passes that rank's shard) */
   int32_t seq_len;          /* S, multiple of 128 */
-  int32_t microbatch_size;  /* B >= 1; T = B*S rows per call, T multiple of 256 */
+  int32_t microbatch_size;  /* B >= 1; T = B*S rows per call (a multiple of 128, as S is) */
   int32_t n_microbatches;   /* K of Eq. 1: micro-batches accumulated per iteration (used by ah_stage_profile) */
   int32_t max_in_flight;    /* activation slots: micro-batches whose forward has run and whose backward has not (1F1B: stages - stage index) */
   int32_t recompute;        /* 0: keep every layer's activations; 1: keep layer inputs only and re-run each layer's forward inside backward */
@@ -179,6 +180,13 @@ int ah_stage_flush_grads(ah_stage_t* st, void* hip_stream);
  * sums are complete once every group has been taken (see above). */
 int ah_stage_grads(ah_stage_t* st, float** dev_ptr, uint64_t* n_elems);
 
+/* Where the stage keeps the input of layer `layer` for the micro-batch in `slot`: device, bf16 [B*S, hidden], read
+ * only, valid from that slot's ah_stage_forward until the slot's next forward.  The input of layer l + 1 is the
+ * output of layer l, so this is the per-layer view of the values that Section III-D's profiler takes of the times
+ * (the stage is a chain of l_i layers, Section III-C Eq. 4): tests read it to see how the error against an exact
+ * evaluation grows with depth.  Kept with and without recompute. */
+int ah_stage_layer_input(ah_stage_t* st, int slot, int layer, const void** dev_ptr);
+
 /* Starts a new accumulation: the next ah_stage_backward overwrites instead of
  * adding (no memset is enqueued; until that backward has run the buffer holds
  * the previous iteration's sums).  A new stage starts in this state.
@@ -232,6 +240,7 @@ int ah_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int nh,
 /* Its backward: dqkv[B*S, 3*nh*d] from qkv, o, lse and do[B*S, nh*d]; `delta` is fp32 scratch [B, nh, S]. */
 int ah_attention_bwd(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, float* delta,
                      int B, int S, int nh, int d, int causal, void* hip_stream);
+
 
 #ifdef __cplusplus
 }

@@ -163,27 +163,47 @@ def attention_probs(q, k, causal=True):
     return e / e.sum(axis=-1, keepdims=True)
 
 
+# The (batch, head) pairs are independent.  HEAD_THREADS > 1 hands them to that many threads (same arithmetic per
+# head, numpy releases the interpreter lock inside its loops); the full-size parity tests set it, nothing else does.
+HEAD_THREADS = 1
+
+
+def _for_each_head(fn, B, nh):
+    pairs = [(b, j) for b in range(B) for j in range(nh)]
+    if HEAD_THREADS <= 1:
+        for b, j in pairs:
+            fn(b, j)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=HEAD_THREADS) as ex:
+            list(ex.map(lambda bj: fn(*bj), pairs))
+
+
 def attention_fwd(q, k, v, causal=True):
     """q, k, v: [B, nh, S, d] -> o same shape."""
     o = np.empty_like(q)
-    for b in range(q.shape[0]):
-        for j in range(q.shape[1]):
-            o[b, j] = attention_probs(q[b, j], k[b, j], causal) @ v[b, j]
+
+    def head(b, j):
+        o[b, j] = attention_probs(q[b, j], k[b, j], causal) @ v[b, j]
+
+    _for_each_head(head, q.shape[0], q.shape[1])
     return o
 
 
 def attention_bwd(q, k, v, do, causal=True):
     dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
     scale = q.dtype.type(1.0 / np.sqrt(q.shape[-1]))
-    for b in range(q.shape[0]):
-        for j in range(q.shape[1]):
-            p = attention_probs(q[b, j], k[b, j], causal)
-            dv[b, j] = p.T @ do[b, j]
-            dp = do[b, j] @ v[b, j].T
-            delta = (p * dp).sum(axis=-1, keepdims=True)
-            ds = p * (dp - delta)
-            dq[b, j] = (ds @ k[b, j]) * scale
-            dk[b, j] = (ds.T @ q[b, j]) * scale
+
+    def head(b, j):
+        p = attention_probs(q[b, j], k[b, j], causal)
+        dv[b, j] = p.T @ do[b, j]
+        dp = do[b, j] @ v[b, j].T
+        delta = (p * dp).sum(axis=-1, keepdims=True)
+        ds = p * (dp - delta)
+        dq[b, j] = (ds @ k[b, j]) * scale
+        dk[b, j] = (ds.T @ q[b, j]) * scale
+
+    _for_each_head(head, q.shape[0], q.shape[1])
     return dq, dk, dv
 
 

@@ -99,6 +99,7 @@ def _load():
     L.ah_gemm_tn_segmented.argtypes = [C.POINTER(vp), C.POINTER(vp), i, vp, i, i, i, i, vp]
     L.ah_attention_fwd.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
     L.ah_attention_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
+    L.ah_stage_layer_input.argtypes = [vp, i, i, C.POINTER(vp)]
     return L
 
 
@@ -167,6 +168,16 @@ class Stage:
         off, r, c = self.param_layout(layer, name)
         v = self.grads[off:off + r * c]
         return v.view(r, c) if r > 1 else v
+
+    def layer_input(self, slot, layer):
+        """bf16 [T, hidden] view of the input the stage keeps for `layer` of the micro-batch in `slot`."""
+        import torch
+        p = C.c_void_p()
+        _check(lib.ah_stage_layer_input(self._h, slot, layer, C.byref(p)))
+        T, h = self.cfg.microbatch_size * self.cfg.seq_len, self.cfg.hidden
+        off = p.value - self.activations.data_ptr()
+        assert 0 <= off and off + 2 * T * h <= self.activations.numel()
+        return self.activations[off:off + 2 * T * h].view(torch.bfloat16).view(T, h)
 
     def forward(self, slot, x, y, stream=None):
         _check(lib.ah_stage_forward(self._h, slot, _ptr(x), _ptr(y), _stream(stream)))

@@ -33,12 +33,6 @@ def build(verbose=False):
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    # stand-alone micro-benchmark of the chip's MFMA and LDS ceilings (not part of the library)
-    tool = os.path.join(HERE, "microbench", "chip_limits.hip")
-    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-                        "-packed-fp32-ops", tool, "-o", os.path.join(OBJ, "chip_limits")], capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed on %s:\n%s" % (tool, r.stderr))
     return LIB
 
 

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <new>
 #include <vector>
 
 using namespace ah;
@@ -66,6 +67,7 @@ extern "C" int ah_cost_partition_layers(int P, int n_layers, const double* t_lay
   if (!t_layer || !mem_bytes || !in_flight || !l_out || !bottleneck || P < 1 || n_layers < P || P > 4096 || n_layers > (1 << 20))
     return set_error(AH_EINVAL, "ah_cost_partition_layers: bad argument (need P >= 1 and n_layers >= P)");
   if (!(fixed_per_layer >= 0.0) || !(act_per_layer >= 0.0)) return set_error(AH_EINVAL, "ah_cost_partition_layers: negative byte counts");
+  try {
   // largest layer count each stage can hold
   std::vector<long> cap(P);
   long cap_sum = 0;
@@ -82,18 +84,13 @@ extern "C" int ah_cost_partition_layers(int P, int n_layers, const double* t_lay
   // The optimum is one of the values l * t_layer[i].  For a candidate tau, stage i can take
   // min(cap_i, number of l with l * t_layer[i] <= tau) layers; tau is feasible when every stage can
   // take one and together they can take n_layers.  The counts use the same product as the candidates.
-  auto fits = [&](int i, double tau) {
-    long lo = 0, hi = cap[i];  // largest l in [0, cap] with l * t <= tau
-    while (lo < hi) {
-      const long mid = (lo + hi + 1) / 2;
-      if ((double)mid * t_layer[i] <= tau) lo = mid; else hi = mid - 1;
-    }
-    return lo;
+  auto fits = [&](int i, double tau) {  // largest l in [0, cap] with l * t <= tau
+    const double q = std::floor(tau / t_layer[i]);
+    long l = q >= (double)cap[i] ? cap[i] : q > 0.0 ? (long)q : 0;
+    while (l < cap[i] && (double)(l + 1) * t_layer[i] <= tau) l++;  // the division may be off by one ulp either way
+    while (l > 0 && (double)l * t_layer[i] > tau) l--;
+    return l;
   };
-  std::vector<double> cand;
-  for (int i = 0; i < P; i++)
-    for (long l = 1; l <= cap[i]; l++) cand.push_back((double)l * t_layer[i]);
-  std::sort(cand.begin(), cand.end());
   auto feasible = [&](double tau) {
     long total = 0;
     for (int i = 0; i < P; i++) {
@@ -103,12 +100,20 @@ extern "C" int ah_cost_partition_layers(int P, int n_layers, const double* t_lay
     }
     return total >= n_layers;
   };
-  size_t lo = 0, hi = cand.size() - 1;  // cand.back() is feasible: every stage at its cap, cap_sum >= n_layers
-  while (lo < hi) {
-    const size_t mid = (lo + hi) / 2;
-    if (feasible(cand[mid])) hi = mid; else lo = mid + 1;
+  // Feasibility grows with tau, so per stage the smallest feasible candidate l * t_layer[i] is found by bisection
+  // over l (no list of all P * n_layers candidates is built); the optimum is the smallest of those.
+  double tau = -1.0;
+  for (int i = 0; i < P; i++) {
+    if (!feasible((double)cap[i] * t_layer[i])) continue;  // none of this stage's candidates is feasible
+    long lo = 1, hi = cap[i];
+    while (lo < hi) {
+      const long mid = (lo + hi) / 2;
+      if (feasible((double)mid * t_layer[i])) hi = mid; else lo = mid + 1;
+    }
+    const double c = (double)lo * t_layer[i];
+    if (tau < 0.0 || c < tau) tau = c;
   }
-  const double tau = cand[lo];
+  if (tau < 0.0) return set_error(AH_EINVAL, "ah_cost_partition_layers: no feasible bottleneck (inconsistent stage times)");
   // every stage gets one layer; the rest goes to the earliest stages that still fit under tau
   long left = n_layers - P;
   for (int i = 0; i < P; i++) l_out[i] = 1;
@@ -121,4 +126,9 @@ extern "C" int ah_cost_partition_layers(int P, int n_layers, const double* t_lay
   for (int i = 0; i < P; i++) worst = std::max(worst, (double)l_out[i] * t_layer[i]);
   *bottleneck = worst;
   return AH_OK;
+  } catch (const std::bad_alloc&) {
+    return set_error(AH_ENOMEM, "ah_cost_partition_layers: out of host memory");
+  } catch (...) {
+    return set_error(AH_EINVAL, "ah_cost_partition_layers: unexpected failure");
+  }
 }

@@ -128,6 +128,9 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
     const int Fu_ = (c->arch == AH_ARCH_LLAMA ? 2 : 1) * s->F;
     const int mn[4][2] = {{s->F, s->h}, {s->h, Fu_}, {s->hl, s->h}, {s->h, 3 * s->hl}};  // WG_FC2, WG_FC1, WG_WO, WG_QKV
     for (int i = 0; i < 4; i++) s->defer_matrix[i] = gemm_tile_area(mn[i][0], mn[i][1], GEMM_TN) >= min_area;
+    // tuning and test aid: the choice given outright, bit i = matrix i (second MLP, first MLP, out-projection, QKV)
+    if (const char* m = getenv("AH_DEFER_MATRICES"))
+      for (int i = 0; i < 4; i++) s->defer_matrix[i] = (atoi(m) >> i) & 1;
   }
   s->eps = c->norm_eps > 0 ? c->norm_eps : (s->llama ? 1e-6f : 1e-5f);
   s->rope_base = c->rope_base > 0 ? c->rope_base : 10000.f;
@@ -472,7 +475,10 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   }
   TRY(wgrad(s, SITE_FC1_WGRAD, layer, WG_FC1, wp, a.c, du, p.g_w1, h, Fu, st, sd));
   TRY(gemm(s, SITE_FC1_DGRAD, GEMM_NT, EPI_BF16, du, Fu, p.w1, Fu, dsm, h, T, h, Fu, nullptr, nullptr, 0, nullptr, 0, st));  // dc
-  if (sd != st) TRY(hipEventRecord(ev[2], sd));  // the side stream is done with du
+  // The side stream is done with du.  Only attention backward may have to wait for that, and only where dqkv
+  // shares du's buffer; an event nobody waits for is not recorded.
+  const bool du_reused = sd != st && dqkv == du;
+  if (du_reused) TRY(hipEventRecord(ev[2], sd));
   // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
   TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part_n2, T, h, st, vp.acc));
   TRY(stream_order(st, sd, ev[3]));
@@ -484,7 +490,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   TRY(wgrad(s, SITE_WO_WGRAD, layer, WG_WO, wp, a.o, dmid, p.g_wo, hl, h, st, sd));
   TRY(gemm(s, SITE_WO_DGRAD, GEMM_NT, EPI_BF16, dmid, h, p.wo, h, dsm, hl, T, hl, h, nullptr, nullptr, 0, nullptr, 0, st));  // do
   // attention (where dqkv shares its buffer with du: wait until the first MLP matrix's weight gradient has read it)
-  if (sd != st && dqkv == du) TRY(hipStreamWaitEvent(st, ev[2], 0));
+  if (du_reused) TRY(hipStreamWaitEvent(st, ev[2], 0));
   TIMED(SITE_ATTN_BWD, launch_attention_bwd(a.qkv, a.o, (const float*)a.lse, dsm, dqkv, delta, B, S, s->nh, s->d, s->causal, st));
   if (s->llama) TIMED(SITE_ROPE, launch_rope(dqkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, -1.f, st));
   TRY(stream_order(st, sd, ev[4]));
@@ -650,6 +656,17 @@ hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipSt
   return hipSuccess;
 }
 
+// A step with deferred weight gradients (group > 1) is not offered for HIP graph capture: replaying such a capture
+// has ended in a host-side fault inside the graph launch whose cause is not known, so the two calls that belong to
+// that mode refuse a capturing stream instead of recording something that may not replay.
+int refuse_capture_of_groups(const ah_stage* s, hipStream_t st, const char* who) {
+  if (s->group <= 1) return AH_OK;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cs) != hipSuccess) { (void)hipGetLastError(); return AH_OK; }  // the legacy default stream cannot be queried while another stream captures
+  if (cs == hipStreamCaptureStatusNone) return AH_OK;
+  return set_error(AH_EUNSUPPORTED, "%s: the stream is being captured into a HIP graph and wgrad_group is %d; graph capture is supported for wgrad_group <= 1 only", who, s->group);
+}
+
 float median(std::vector<float>& v) {
   std::sort(v.begin(), v.end());
   return v.empty() ? 0.f : v[v.size() / 2];
@@ -738,12 +755,14 @@ extern "C" int ah_stage_backward(ah_stage_t* st, int slot, const void* dy, void*
   if (!st || !dy || !dx) return set_error(AH_EINVAL, "ah_stage_backward: NULL argument");
   if (slot < 0 || slot >= (int)st->busy.size()) return set_error(AH_EINVAL, "ah_stage_backward: slot %d out of range [0, %zu)", slot, st->busy.size());
   if (st->busy[slot] != 1) return set_error(AH_ESTATE, "ah_stage_backward: slot %d holds no forward pass awaiting backward", slot);
+  if (int rc = refuse_capture_of_groups(st, (hipStream_t)stream, "ah_stage_backward")) return rc;
   return hip_status(stage_backward(st, slot, dy, dx, (hipStream_t)stream, nullptr), "ah_stage_backward");
 }
 
 extern "C" int ah_stage_flush_grads(ah_stage_t* st, void* stream) {
   discard_stale_hip_error();
   if (!st) return set_error(AH_EINVAL, "ah_stage_flush_grads: NULL argument");
+  if (int rc = refuse_capture_of_groups(st, (hipStream_t)stream, "ah_stage_flush_grads")) return rc;
   return hip_status(flush_wgrads(st, (hipStream_t)stream), "ah_stage_flush_grads");
 }
 
@@ -751,6 +770,14 @@ extern "C" int ah_stage_grads(ah_stage_t* st, float** dev_ptr, uint64_t* n_elems
   if (!st || !dev_ptr || !n_elems) return set_error(AH_EINVAL, "ah_stage_grads: NULL argument");
   *dev_ptr = (float*)st->bufs.grads;
   *n_elems = st->layer_elems * st->L;
+  return AH_OK;
+}
+
+extern "C" int ah_stage_layer_input(ah_stage_t* st, int slot, int layer, const void** dev_ptr) {
+  if (!st || !dev_ptr) return set_error(AH_EINVAL, "ah_stage_layer_input: NULL argument");
+  if (slot < 0 || slot >= (int)st->busy.size()) return set_error(AH_EINVAL, "ah_stage_layer_input: slot %d out of range [0, %zu)", slot, st->busy.size());
+  if (layer < 0 || layer >= st->L) return set_error(AH_EINVAL, "ah_stage_layer_input: layer %d out of range [0, %d)", layer, st->L);
+  *dev_ptr = act_ptrs(st, slot, layer).x_in;
   return AH_OK;
 }
 

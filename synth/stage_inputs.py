@@ -11,7 +11,7 @@ shard the full layer is drawn and rank r's contiguous block is sliced out
 import numpy as np
 
 __all__ = ["WORKLOADS", "BASE_SEED", "f32_to_bf16_bits", "bf16_bits_to_f32", "round_bf16",
-           "local_dims", "param_spec", "draw_layer_params", "draw_activation",
+           "local_dims", "param_spec", "draw_layer_params", "draw_stage_params", "draw_activation",
            "slice_column_parallel", "slice_row_parallel", "slice_qkv_columns"]
 
 BASE_SEED = 20953
@@ -31,17 +31,26 @@ WORKLOADS = {
 
 def f32_to_bf16_bits(a):
     """float32 array -> uint16 array of bf16 bit patterns, round to nearest even."""
-    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
-    rounded = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
-    return (rounded >> np.uint32(16)).astype(np.uint16)
+    return (_rne_high_half(a) >> np.uint32(16)).astype(np.uint16)
 
 
 def bf16_bits_to_f32(b):
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def _rne_high_half(a):
+    """uint32 view of a float32 array with the low 16 bits rounded away (to nearest, ties to even) and zeroed."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = u >> np.uint32(16)
+    r &= np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    r &= np.uint32(0xFFFF0000)
+    return r
+
+
 def round_bf16(a):
-    return bf16_bits_to_f32(f32_to_bf16_bits(a)).reshape(np.shape(a))
+    return _rne_high_half(a).view(np.float32).reshape(np.shape(a))
 
 
 def local_dims(w):
@@ -93,6 +102,30 @@ def slice_qkv_columns(w, tp, r):
     return np.concatenate([slice_column_parallel(w[..., b * third:(b + 1) * third], tp, r) for b in range(3)], axis=-1)
 
 
+def _draw_param(w, layer, idx, name, shape, kind, seed, tp_rank, perturb_vectors):
+    tp = w["tp"]
+    tid = 1000 * (layer + 1) + idx
+    if kind == "w":
+        t = _normal_bf16(seed, tid, shape, 0.02)
+    elif perturb_vectors:
+        t = _normal_bf16(seed, tid, shape, 0.1) + (1.0 if kind == "one" else 0.0)
+        t = round_bf16(t.astype(np.float32))
+    else:
+        t = np.full(shape, 1.0 if kind == "one" else 0.0, dtype=np.float32)
+    if tp > 1:
+        if name in ("wqkv", "bqkv"):
+            t = slice_qkv_columns(t, tp, tp_rank)
+        elif name in ("w1", "b1"):
+            t = slice_column_parallel(t, tp, tp_rank)
+        elif name == "wgu":
+            half = t.shape[-1] // 2
+            t = np.concatenate([slice_column_parallel(t[:, :half], tp, tp_rank),
+                                slice_column_parallel(t[:, half:], tp, tp_rank)], axis=-1)
+        elif name in ("wo", "w2", "wd"):
+            t = slice_row_parallel(t, tp, tp_rank)
+    return np.ascontiguousarray(t, dtype=np.float32)
+
+
 def draw_layer_params(w, layer, seed=BASE_SEED, tp_rank=0, perturb_vectors=False):
     """Rank tp_rank's shard of layer `layer`: dict name -> float32 array holding bf16 values.
 
@@ -100,29 +133,30 @@ def draw_layer_params(w, layer, seed=BASE_SEED, tp_rank=0, perturb_vectors=False
     parameters by small random values (used by tests that would otherwise not
     see a wrong bias or gain path)."""
     h_full = w["n_heads"] * w["head_dim"]
-    tp = w["tp"]
-    out = {}
-    for idx, (name, shape, kind) in enumerate(param_spec(w["arch"], w["hidden"], h_full, w["ffn"])):
-        tid = 1000 * (layer + 1) + idx
-        if kind == "w":
-            t = _normal_bf16(seed, tid, shape, 0.02)
-        elif perturb_vectors:
-            t = _normal_bf16(seed, tid, shape, 0.1) + (1.0 if kind == "one" else 0.0)
-            t = round_bf16(t.astype(np.float32))
-        else:
-            t = np.full(shape, 1.0 if kind == "one" else 0.0, dtype=np.float32)
-        if tp > 1:
-            if name in ("wqkv", "bqkv"):
-                t = slice_qkv_columns(t, tp, tp_rank)
-            elif name in ("w1", "b1"):
-                t = slice_column_parallel(t, tp, tp_rank)
-            elif name == "wgu":
-                half = t.shape[-1] // 2
-                t = np.concatenate([slice_column_parallel(t[:, :half], tp, tp_rank),
-                                    slice_column_parallel(t[:, half:], tp, tp_rank)], axis=-1)
-            elif name in ("wo", "w2", "wd"):
-                t = slice_row_parallel(t, tp, tp_rank)
-        out[name] = np.ascontiguousarray(t, dtype=np.float32)
+    return {name: _draw_param(w, layer, idx, name, shape, kind, seed, tp_rank, perturb_vectors)
+            for idx, (name, shape, kind) in enumerate(param_spec(w["arch"], w["hidden"], h_full, w["ffn"]))}
+
+
+def draw_stage_params(w, seed=BASE_SEED, tp_rank=0, perturb_vectors=False, workers=1):
+    """draw_layer_params for every layer of the stage; the tensors (each its own stream: same values) are drawn by
+    `workers` threads, which is what makes the multi-billion-parameter stages affordable in a test."""
+    h_full = w["n_heads"] * w["head_dim"]
+    spec = param_spec(w["arch"], w["hidden"], h_full, w["ffn"])
+    jobs = [(l, idx) + spec[idx] for l in range(w["n_layers"]) for idx in range(len(spec))]
+    jobs.sort(key=lambda j: -int(np.prod(j[3])))     # largest first
+    out = [dict.fromkeys(n for n, _, _ in spec) for _ in range(w["n_layers"])]
+
+    def one(job):
+        l, idx, name, shape, kind = job
+        out[l][name] = _draw_param(w, l, idx, name, shape, kind, seed, tp_rank, perturb_vectors)
+
+    if workers <= 1:
+        for j in jobs:
+            one(j)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(one, jobs))
     return out
 
 

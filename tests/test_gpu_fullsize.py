@@ -93,9 +93,17 @@ def test_attention_at_benchmark_shapes_sampled_heads(B, S, nh, d, causal):
         do = d_o[rows, j * d:(j + 1) * d].astype(np.float64)[None, None]
         ro = R.attention_fwd(q, k, v, causal)[0, 0]
         rdq, rdk, rdv = (t[0, 0] for t in R.attention_bwd(q, k, v, do, causal))
-        assert U.rel_l2(o_np[rows, j * d:(j + 1) * d], ro) <= 2e-2
+        e = U.error_views(o_np[rows, j * d:(j + 1) * d], ro)
+        assert e["l2"] <= 2e-2 and e["rows"] <= 2e-2 and e["maxabs"] <= 2e-2, (b, j, e)
         for blk, ref in enumerate((rdq, rdk, rdv)):
-            assert U.rel_l2(dqkv_np[rows, blk * hl + j * d: blk * hl + (j + 1) * d], ref) <= 3e-2, (b, j, blk)
+            e = U.error_views(dqkv_np[rows, blk * hl + j * d: blk * hl + (j + 1) * d], ref)
+            # Per row (one query's dq, one key's dk / dv) the bound is looser than per tensor.  The kernels take
+            # delta_i = sum_k p_ik dp_ik as do_i . o_i from the stored bf16 output, an absolute error of about
+            # 2^-9 |do_i| |o_i| / sqrt(3) in every dp_ik - delta_i of the row; where the softmax of a row is peaked
+            # (few keys: the first queries) the exact differences are themselves small and that error is a sizeable
+            # fraction of the row (6e-2 seen at query 1), while over many keys it averages out (3e-3 per tensor).
+            # A wrong row has error ~1.
+            assert e["l2"] <= 3e-2 and e["maxabs"] <= 3e-2 and e["rows"] <= 0.15, (b, j, blk, e)
         # log-sum-exp of the scaled (causal: masked) scores, from its definition
         s = (q[0, 0] @ k[0, 0].T) / np.sqrt(d)
         if causal:
@@ -105,18 +113,82 @@ def test_attention_at_benchmark_shapes_sampled_heads(B, S, nh, d, causal):
         assert np.abs(lse_np[b, j] - ref_lse).max() <= 2e-2
 
 
+HOST_THREADS = 16   # the GPU machine's CPU share
+
+
+@pytest.fixture
+def threaded_oracle():
+    R.HEAD_THREADS = HOST_THREADS
+    yield
+    R.HEAD_THREADS = 1
+
+
 @pytest.mark.parametrize("name", ["gpt1p3b", "gpt7b_tp2", "gpt13b", "llama7b", "bert_large"])
-def test_one_full_size_layer_of_each_workload(name):
+def test_one_full_size_layer_of_each_workload(name, threaded_oracle):
     w = dict(SI.WORKLOADS[name], n_layers=1, n_mb=1)
     gcfg, ocfg = U.make_cfgs(w)
-    params = [SI.draw_layer_params(w, 0, perturb_vectors=True)]
+    params = SI.draw_stage_params(w, perturb_vectors=True, workers=HOST_THREADS)
     xs, dys = [SI.draw_activation(w, "x", 0)], [SI.draw_activation(w, "dy", 0)]
     st = P.Stage(gcfg)
     U.load_params(st, params)
     ys, dxs = U.run_gpu(st, xs, dys)
     o_ys, o_dxs, o_grads = U.run_oracle(ocfg, params, xs, dys, np.float32)
-    wa, wg = U.compare_stage(st, params, ys, dxs, o_ys, o_dxs, o_grads)
-    print("%s: worst activation err %.3e, worst gradient err %.3e" % (name, wa, wg))
+    rep = {}
+    wa, wg = U.compare_stage(st, params, ys, dxs, o_ys, o_dxs, o_grads, report=rep)
+    print("%s: worst activation err %.3e, worst gradient err %.3e; %s" % (name, wa, wg, rep))
+
+
+def _keep(name, rep, n_mb, w, seconds):
+    """The error figures of a full-depth case, kept beside the run's other results when that folder exists (never read back)."""
+    import json
+    import os
+    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(out):
+        with open(os.path.join(out, "full_depth_%s.json" % name), "w") as f:
+            json.dump(dict(rep, workload=name, micro_batches=n_mb, layers=w["n_layers"], seconds=seconds), f)
+
+
+# workload -> micro-batches run through the oracle: every one of gpt1p3b's, the first two of the larger stages
+FULL_DEPTH = {"gpt1p3b": 8, "gpt7b_tp2": 2, "gpt13b": 2, "llama7b": 2}
+
+
+@pytest.mark.parametrize("name", list(FULL_DEPTH))
+def test_full_depth_stage_against_the_oracle(name, threaded_oracle, capsys):
+    """Every workload of the table with all its layers (4, 4, 10 and 8 with recomputation) and as the library runs
+    it in the benchmark: what the planner balances is the time of the whole stage of l_i layers over the K
+    micro-batches of an iteration (Section III-A Eq. 1, Section III-C Eq. 4), so the values are checked for the
+    whole stage too.  y and dx of each micro-batch, every layer's output, and every parameter gradient accumulated
+    over the micro-batches, against the float32 oracle on the same seeded inputs."""
+    import time
+    t0 = time.time()
+
+    def say(msg):
+        with capsys.disabled():
+            print("[full depth %s, %4.0f s] %s" % (name, time.time() - t0, msg), flush=True)
+
+    n_mb = FULL_DEPTH[name]
+    w = dict(SI.WORKLOADS[name], n_mb=n_mb)
+    gcfg, ocfg = U.make_cfgs(w)
+    params = SI.draw_stage_params(w, perturb_vectors=True, workers=HOST_THREADS)
+    xs = [SI.draw_activation(w, "x", m) for m in range(n_mb)]
+    dys = [SI.draw_activation(w, "dy", m) for m in range(n_mb)]
+    say("inputs drawn")
+    st = P.Stage(gcfg)
+    U.load_params(st, params)
+    taps = []
+    ys, dxs = U.run_gpu(st, xs, dys, taps=taps)
+    say("GPU passes done")
+    o_outs = []
+    o_ys, o_dxs, o_grads = U.run_oracle(ocfg, params, xs, dys, np.float32, outs=o_outs, progress=say)
+    rep = {}
+    try:
+        wa, wg = U.compare_stage(st, params, ys, dxs, o_ys, o_dxs, o_grads, taps=taps, o_outs=o_outs, report=rep)
+    finally:
+        _keep(name, rep, n_mb, w, time.time() - t0)
+    say("worst activation err %.3e, worst gradient err %.3e" % (wa, wg))
+    say("rows %.3e (%s), act max-abs %.3e, grad tiles %.3e (%s), grad max-abs %.3e"
+        % (rep["act_rows"], rep.get("act_rows_where"), rep["act_maxabs"], rep["grad_tiles"], rep.get("grad_tiles_where"), rep["grad_maxabs"]))
+    say("per-layer output err " + " ".join("%.2e" % e for e in rep["layer_l2"]))
 
 
 def test_benchmark_iteration_properties():

@@ -241,6 +241,18 @@ def test_accumulation_equals_concatenated_batch(arch):
             assert np.allclose(ga[k], gc[k], rtol=1e-10, atol=1e-11), k
 
 
+def test_head_threads_change_no_bit():
+    rng = np.random.default_rng(61)
+    q, k, v, do = (rng.standard_normal((2, 3, 17, 8)) for _ in range(4))
+    one = (R.attention_fwd(q, k, v, True),) + R.attention_bwd(q, k, v, do, True)
+    R.HEAD_THREADS = 4
+    try:
+        many = (R.attention_fwd(q, k, v, True),) + R.attention_bwd(q, k, v, do, True)
+    finally:
+        R.HEAD_THREADS = 1
+    assert all(np.array_equal(a, b) for a, b in zip(one, many))
+
+
 # ---------------------------------------------------------------- tensor-parallel partial sums
 @pytest.mark.parametrize("arch", ["gpt", "llama", "bert"])
 def test_shard_partials_sum_to_unsharded_block(arch):
@@ -255,6 +267,14 @@ def test_shard_partials_sum_to_unsharded_block(arch):
     assert np.allclose(att, R.attn_block_partial(full, p, x), rtol=1e-11, atol=1e-12)
     mlp = sum(R.mlp_block_partial(loc, s, x) for s in shards)
     assert np.allclose(mlp, R.mlp_block_partial(full, p, x), rtol=1e-11, atol=1e-12)
+    # the helper against the layer itself (the sum above compares it only with itself): the MLP block's addend is
+    # what the layer adds to x_mid, less the bias that is added after the reduce point
+    y, cf = R.layer_fwd(full, p, x)
+    addend = y - cf["x_mid"] - (p["b2"] if full.gpt_block else 0.0)
+    assert np.abs(addend).max() > 1e-3
+    assert np.allclose(R.mlp_block_partial(full, p, cf["x_mid"]), addend, rtol=1e-10, atol=1e-12)
+    # likewise the attention block's addend: x_mid - x - bo
+    assert np.allclose(R.attn_block_partial(full, p, x), cf["x_mid"] - x - (p["bo"] if full.gpt_block else 0.0), rtol=1e-10, atol=1e-12)
     # backward: with the same upstream gradient, each shard's gradient of the row-cut
     # matrix is the matching row block of the unsharded one (gradients are shaped like their shard)
     dy = rng.standard_normal((2 * S, h))
