@@ -242,6 +242,18 @@ int ah_attention_bwd(const void* qkv, const void* o, const float* lse, const voi
                      int B, int S, int nh, int d, int causal, void* hip_stream);
 
 
+/* ah_attention_bwd for callers that cannot allocate device memory or hand over scratch: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same output, same kernels; the
+ * fp32 scratch [B, nh, S] that ah_attention_bwd takes as `delta` lives in a fixed array inside the library's
+ * device image instead (1 MiB per GPU, held until the process ends), so B * nh * S must not exceed
+ * AH_ATTENTION_STATIC_MAX_ROWS (else AH_EINVAL, nothing is launched).  The call allocates nothing and frees
+ * nothing.  The device that holds the buffers must be the calling thread's current device.  Every call on a GPU
+ * uses that GPU's one array (fully rewritten by each call before it is read): calls that overlap on one GPU, on
+ * different streams or from different threads, race; calls in stream order on one stream do not. */
+#define AH_ATTENTION_STATIC_MAX_ROWS 262144
+int ah_attention_bwd_static(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
+                            int B, int S, int nh, int d, int causal, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

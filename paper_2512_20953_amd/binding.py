@@ -99,6 +99,7 @@ def _load():
     L.ah_gemm_tn_segmented.argtypes = [C.POINTER(vp), C.POINTER(vp), i, vp, i, i, i, i, vp]
     L.ah_attention_fwd.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
     L.ah_attention_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
+    L.ah_attention_bwd_static.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, vp]
     L.ah_stage_layer_input.argtypes = [vp, i, i, C.POINTER(vp)]
     return L
 
@@ -247,6 +248,13 @@ def attention_fwd(qkv, o, lse, B, S, nh, d, causal=True, stream=None):
 
 def attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, causal=True, stream=None):
     _check(lib.ah_attention_bwd(_ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(delta), B, S, nh, d, int(bool(causal)), _stream(stream)))
+
+
+ATTENTION_STATIC_MAX_ROWS = 262144
+
+
+def attention_bwd_static(qkv, o, lse, d_o, dqkv, B, S, nh, d, causal=True, stream=None):
+    _check(lib.ah_attention_bwd_static(_ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dqkv), B, S, nh, d, int(bool(causal)), _stream(stream)))
 
 
 # ---- cost model (include/ah_cost.h): host arrays in, numbers out

@@ -11,6 +11,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -937,4 +938,39 @@ extern "C" int ah_attention_bwd(const void* qkv, const void* o, const float* lse
   if (!qkv || !o || !lse || !d_o || !dqkv || !delta) return set_error(AH_EINVAL, "ah_attention_bwd: NULL pointer");
   if (B < 1 || nh < 1 || S < 1 || S % 128 || (d != 64 && d != 128)) return set_error(AH_EUNSUPPORTED, "ah_attention_bwd: need S %% 128 == 0 and d in {64, 128}");
   return hip_status(launch_attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, causal != 0, (hipStream_t)stream), "ah_attention_bwd");
+}
+
+// ---- the entry point that allocates nothing: attention backward with its scratch in the device image
+namespace {
+// One copy per GPU, at its own address on each; in host code the name below is only a handle for
+// hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) float scratch[AH_ATTENTION_STATIC_MAX_ROWS];
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device, looked up once
+std::mutex g_scratch_mu;
+}  // namespace
+
+extern "C" int ah_attention_bwd_static(const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv, int B, int S,
+                                       int nh, int d, int causal, void* stream) {
+  discard_stale_hip_error();
+  if (!qkv || !o || !lse || !d_o || !dqkv) return set_error(AH_EINVAL, "ah_attention_bwd_static: NULL pointer");
+  if (B < 1 || nh < 1 || S < 1 || S % 128 || (d != 64 && d != 128)) return set_error(AH_EUNSUPPORTED, "ah_attention_bwd_static: need S %% 128 == 0 and d in {64, 128}");
+  if ((long)B * nh * S > (long)AH_ATTENTION_STATIC_MAX_ROWS)
+    return set_error(AH_EINVAL, "ah_attention_bwd_static: B * nh * S = %ld exceeds the fixed scratch of %d rows (use ah_attention_bwd with a caller-supplied buffer)", (long)B * nh * S, AH_ATTENTION_STATIC_MAX_ROWS);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_status(e, "ah_attention_bwd_static (hipGetDevice)");
+  if (dev < 0 || dev >= kMaxDevices) return set_error(AH_EUNSUPPORTED, "ah_attention_bwd_static: device index %d out of range", dev);
+  float* delta;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) return hip_status(e != hipSuccess ? e : hipErrorInvalidSymbol, "ah_attention_bwd_static (hipGetSymbolAddress)");
+      g_scratch_ptr[dev] = (float*)p;
+    }
+    delta = g_scratch_ptr[dev];
+  }
+  return hip_status(launch_attention_bwd(qkv, o, lse, d_o, dqkv, delta, B, S, nh, d, causal != 0, (hipStream_t)stream), "ah_attention_bwd_static");
 }
