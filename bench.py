@@ -103,7 +103,7 @@ def main():
     G = args.wgrad_group if args.wgrad_group > 0 else (1 if w["recompute"] else min(w["n_mb"], 16))
     cfg = P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
                              head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
-                             max_in_flight=G, recompute=w["recompute"], wgrad_group=G)
+                             max_in_flight=G, recompute=w["recompute"], wgrad_group=G, residual_fp32=w.get("res32", 0))
     st = P.Stage(cfg, device=dev)
     # synthetic weights of the stated distribution, generated on the device: N(0, 0.02), gains 1, biases 0
     st.params.normal_(0.0, 0.02)
@@ -203,7 +203,7 @@ def main():
         torch.cuda.empty_cache()
         cfg1 = P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
                                   head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
-                                  max_in_flight=1, recompute=w["recompute"], wgrad_group=1)
+                                  max_in_flight=1, recompute=w["recompute"], wgrad_group=1, residual_fp32=w.get("res32", 0))
         st1 = P.Stage(cfg1, device=dev)
         st1.params.normal_(0.0, 0.02)
         for l in range(w["n_layers"]):
@@ -239,7 +239,7 @@ def main():
            "config": {"workload": args.workload, "arch": w["arch"], "layers": w["n_layers"], "hidden": w["hidden"],
                       "local_heads": w["n_heads"] // w["tp"], "head_dim": w["head_dim"], "local_ffn": w["ffn"] // w["tp"],
                       "seq_len": w["seq"], "microbatch": w["mb"], "microbatches": K, "tokens_per_step": tokens,
-                      "tp_degree": w["tp"], "recompute": w["recompute"], "wgrad_group": G, "parallelism": "1 GPU (one TP shard of one stage)"},
+                      "tp_degree": w["tp"], "recompute": w["recompute"], "residual_fp32": w.get("res32", 0), "wgrad_group": G, "parallelism": "1 GPU (one TP shard of one stage)"},
            "roofline": roofline, "per_microbatch_accumulation": ungrouped,
            "sites": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in s.items()} for s in sites]}
     if not args.no_cpu_baseline:

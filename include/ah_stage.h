@@ -103,6 +103,11 @@ typedef struct {
                              * output-gradient operands (2*T*(2*hidden + first-MLP width + 3*local attention width) bytes each). */
   float norm_eps;           /* 0 selects the default: 1e-5 (GPT), 1e-6 (LLaMA) */
   float rope_base;          /* 0 selects 10000 */
+  int32_t residual_fp32;    /* 0: the residual stream between the blocks (layer inputs, x + attention block) is bf16 like
+                             * every other activation.  1: it is carried and saved in fp32 inside the stage (x and y at the
+                             * boundary stay bf16): each layer then adds its two blocks to an unrounded sum, which removes the
+                             * largest single source of forward error of a deep stage (the error of a stage of l_i layers,
+                             * Section III-C Eq. 4, grows with l_i) at the cost of 4*T*hidden more bytes per saved layer. */
 } ah_stage_config_t;
 
 typedef struct {
@@ -180,8 +185,8 @@ int ah_stage_flush_grads(ah_stage_t* st, void* hip_stream);
  * sums are complete once every group has been taken (see above). */
 int ah_stage_grads(ah_stage_t* st, float** dev_ptr, uint64_t* n_elems);
 
-/* Where the stage keeps the input of layer `layer` for the micro-batch in `slot`: device, bf16 [B*S, hidden], read
- * only, valid from that slot's ah_stage_forward until the slot's next forward.  The input of layer l + 1 is the
+/* Where the stage keeps the input of layer `layer` for the micro-batch in `slot`: device, [B*S, hidden] in bf16 (fp32
+ * with residual_fp32 = 1), read only, valid from that slot's ah_stage_forward until the slot's next forward.  The input of layer l + 1 is the
  * output of layer l, so this is the per-layer view of the values that Section III-D's profiler takes of the times
  * (the stage is a chain of l_i layers, Section III-C Eq. 4): tests read it to see how the error against an exact
  * evaluation grows with depth.  Kept with and without recompute. */
@@ -224,6 +229,10 @@ const char* ah_last_error(void);
 
 /* C[M,N] (bf16) = A[M,K] B[K,N] + bias[N] (bias may be NULL).  M, N and K multiples of 128. */
 int ah_gemm_nn(const void* A, const void* B, const void* bias, void* C, int M, int N, int K, void* hip_stream);
+/* The first product of the SwiGLU block with its activation fused (the LLaMA-style stage's MLP, first matrix cut by
+ * columns as in Section II-B): B[K, 2F] holds gate | up; U[M, 2F] (bf16) = A B, Mout[M, F] (bf16) =
+ * silu(U[:, :F]) * U[:, F:] evaluated on the fp32 sums before they are rounded.  M, F and K multiples of 128. */
+int ah_gemm_nn_swiglu(const void* A, const void* B, void* U, void* Mout, int M, int F, int K, void* hip_stream);
 /* C[M,N] (bf16) = A[M,K] B[N,K]^T.  Same constraints. */
 int ah_gemm_nt(const void* A, const void* B, void* C, int M, int N, int K, void* hip_stream);
 /* C[M,N] (fp32) = beta * C + A[K,M]^T B[K,N], beta in {0, 1}.  Same constraints. */

@@ -28,13 +28,13 @@ class StageConfig(C.Structure):
                 ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn_hidden", C.c_int32), ("tp_degree", C.c_int32),
                 ("tp_rank", C.c_int32), ("seq_len", C.c_int32), ("microbatch_size", C.c_int32),
                 ("n_microbatches", C.c_int32), ("max_in_flight", C.c_int32), ("recompute", C.c_int32),
-                ("wgrad_group", C.c_int32), ("norm_eps", C.c_float), ("rope_base", C.c_float)]
+                ("wgrad_group", C.c_int32), ("norm_eps", C.c_float), ("rope_base", C.c_float), ("residual_fp32", C.c_int32)]
 
     @classmethod
     def make(cls, arch="gpt", n_layers=1, hidden=256, n_heads=4, head_dim=64, ffn=1024, tp=1, tp_rank=0, seq=128, mb=1,
-             n_mb=1, max_in_flight=1, recompute=0, wgrad_group=0, norm_eps=0.0, rope_base=0.0):
+             n_mb=1, max_in_flight=1, recompute=0, wgrad_group=0, norm_eps=0.0, rope_base=0.0, residual_fp32=0):
         return cls(C.sizeof(cls), _ARCH[arch], n_layers, hidden, n_heads, head_dim,
-                   ffn, tp, tp_rank, seq, mb, n_mb, max_in_flight, recompute, wgrad_group, norm_eps, rope_base)
+                   ffn, tp, tp_rank, seq, mb, n_mb, max_in_flight, recompute, wgrad_group, norm_eps, rope_base, residual_fp32)
 
 
 class _Sizes(C.Structure):
@@ -95,6 +95,7 @@ def _load():
     L.ah_cost_partition_layers.argtypes = [i, i, dp, dp, C.c_double, C.c_double, ip, ip, dp]
     L.ah_gemm_nn.argtypes = [vp, vp, vp, vp, i, i, i, vp]
     L.ah_gemm_nt.argtypes = [vp, vp, vp, i, i, i, vp]
+    L.ah_gemm_nn_swiglu.argtypes = [vp, vp, vp, vp, i, i, i, vp]
     L.ah_gemm_tn.argtypes = [vp, vp, vp, i, i, i, i, vp]
     L.ah_gemm_tn_segmented.argtypes = [C.POINTER(vp), C.POINTER(vp), i, vp, i, i, i, i, vp]
     L.ah_attention_fwd.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
@@ -171,14 +172,15 @@ class Stage:
         return v.view(r, c) if r > 1 else v
 
     def layer_input(self, slot, layer):
-        """bf16 [T, hidden] view of the input the stage keeps for `layer` of the micro-batch in `slot`."""
+        """[T, hidden] view (bf16, or fp32 with residual_fp32) of the input the stage keeps for `layer` of the micro-batch in `slot`."""
         import torch
         p = C.c_void_p()
         _check(lib.ah_stage_layer_input(self._h, slot, layer, C.byref(p)))
         T, h = self.cfg.microbatch_size * self.cfg.seq_len, self.cfg.hidden
+        dt, nb = (torch.float32, 4) if self.cfg.residual_fp32 else (torch.bfloat16, 2)
         off = p.value - self.activations.data_ptr()
-        assert 0 <= off and off + 2 * T * h <= self.activations.numel()
-        return self.activations[off:off + 2 * T * h].view(torch.bfloat16).view(T, h)
+        assert 0 <= off and off + nb * T * h <= self.activations.numel()
+        return self.activations[off:off + nb * T * h].view(dt).view(T, h)
 
     def forward(self, slot, x, y, stream=None):
         _check(lib.ah_stage_forward(self._h, slot, _ptr(x), _ptr(y), _stream(stream)))
@@ -222,6 +224,11 @@ class Stage:
 def gemm_nn(A, B, bias, Cout, stream=None):
     M, K = A.shape
     _check(lib.ah_gemm_nn(_ptr(A), _ptr(B), _ptr(bias), _ptr(Cout), M, B.shape[1], K, _stream(stream)))
+
+
+def gemm_nn_swiglu(A, B, U, Mout, stream=None):
+    M, K = A.shape
+    _check(lib.ah_gemm_nn_swiglu(_ptr(A), _ptr(B), _ptr(U), _ptr(Mout), M, B.shape[1] // 2, K, _stream(stream)))
 
 
 def gemm_nt(A, B, Cout, stream=None):

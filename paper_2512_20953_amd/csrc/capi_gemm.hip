@@ -17,6 +17,16 @@ extern "C" int ah_gemm_nn(const void* A, const void* B, const void* bias, void* 
   return hip_status(launch_gemm(GEMM_NN, EPI_BF16, g, (hipStream_t)stream), "ah_gemm_nn");
 }
 
+extern "C" int ah_gemm_nn_swiglu(const void* A, const void* B, void* U, void* Mout, int M, int F, int K, void* stream) {
+  discard_stale_hip_error();
+  if (!A || !B || !U || !Mout) return set_error(AH_EINVAL, "ah_gemm_nn_swiglu: NULL pointer");
+  if (F <= 0 || F > (1 << 29) || !gemm_shape_ok(M, 2 * F, K) || F % 128) return set_error(AH_EUNSUPPORTED, "ah_gemm_nn_swiglu: M, F, K must be positive multiples of 128");
+  GemmArgs g = {};
+  g.A = A; g.B = B; g.C = U; g.C2 = Mout;
+  g.lda = K; g.ldb = 2 * F; g.ldc = 2 * F; g.ldc2 = F; g.swiglu_F = F; g.M = M; g.N = 2 * F; g.K = K;
+  return hip_status(launch_gemm(GEMM_NN, EPI_SWIGLU, g, (hipStream_t)stream), "ah_gemm_nn_swiglu");
+}
+
 extern "C" int ah_gemm_nt(const void* A, const void* B, void* C, int M, int N, int K, void* stream) {
   discard_stale_hip_error();
   if (!A || !B || !C) return set_error(AH_EINVAL, "ah_gemm_nt: NULL pointer");

@@ -52,6 +52,11 @@ __device__ __forceinline__ float gelu_grad_f(float u) {
   return s * __builtin_fmaf(2.0f * u * (1.0f - s), AH_KAPPA * __builtin_fmaf(0.134145f, u * u, 1.0f), 1.0f);
 }
 
+// silu(x) = x sigma(x) through the hardware exp2 and reciprocal
+__device__ __forceinline__ float silu_f(float x) {
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
+
 // s_waitcnt immediate (gfx9 encoding): vmcnt = n (6 bits, split), lgkmcnt = 0, expcnt untouched
 constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 

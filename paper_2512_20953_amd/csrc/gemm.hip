@@ -21,58 +21,62 @@
 
 namespace ah {
 
-// Two pipelines share the tile mapping and the epilogue.  The forward and input-gradient products (at least
-// one k-contiguous operand) use 64-wide k tiles in a ring of five operand buffers, so that every loader
-// instruction fetches whole 128-byte lines of the k-contiguous operand; the weight gradient (both operands
-// k-strided, rows of a tile are 256 or 512 bytes anyway) keeps 32-wide k stages in a ring of four, whose loads
-// all run 2.5 stages ahead.  Measured in the stage: the first is 2-13 % faster on the former products, the
-// second 1-5 % faster on the latter.
-namespace k64 {
-constexpr int BK = 64;  // k-extent of one operand tile in LDS (128 bytes per row of a k-contiguous operand: whole cache lines)
-constexpr int NB = 5;   // operand tiles in the LDS ring (A and B tiles alternate): 2.5 k-blocks of 64
+// Two pipelines share the tile mapping, the LDS layouts, the fragment reads and the epilogue.  The forward and
+// input-gradient products (at least one k-contiguous operand) use 64-wide k tiles in a ring of five operand
+// buffers, so that every loader instruction fetches whole 128-byte lines of the k-contiguous operand; the weight
+// gradient (both operands k-strided, rows of a tile are 256 or 512 bytes anyway) keeps 32-wide k stages in a ring of
+// four, whose loads all run 2.5 stages ahead.  Measured in the stage: the first is 2-13 % faster on the former
+// products, the second 1-5 % faster on the latter.
 
 // ---------------------------------------------------------------------------
-// LDS layouts (all permutations are of 16-byte pieces, the unit of the loader)
-//  k-contiguous tile: [rows][64 k]; row = 128 B = 8 pieces; piece p of row r is
-//    stored at piece p ^ ((r >> 1) & 7): 16 consecutive rows hit 16 distinct
-//    16-byte bank groups for the fragment reads.  A loader instruction fetches
-//    8 rows x 128 B: full cache lines (64-byte row pieces, as a 32-wide k-block
-//    would give, cost the memory pipeline twice the requests and showed up as
-//    ~10 % of MFMA utilisation).
-//  k-strided tile: [64 k][W cols]; row = 2W bytes; the 64-byte granule g of row
-//    k is stored at granule g ^ (k & 3): the 4 rows x 64 B that half a wave
-//    fetches in one transposing read cover all banks once.
+// LDS layouts, for a tile of BK = 64 or 32 k-values (all permutations are of 16-byte pieces, the unit of the loader)
+//  k-contiguous tile: [rows][BK k]; row = 2 BK bytes = BK/8 pieces; piece p of row r is stored at piece
+//    p ^ ((r >> 1) & 7) (BK = 64) or p ^ ((r >> 2) & 3) (BK = 32): 16 consecutive rows hit 16 distinct 16-byte bank
+//    groups for the fragment reads.  With BK = 64 a loader instruction fetches 8 rows x 128 B: full cache lines
+//    (64-byte row pieces, as BK = 32 gives, cost the memory pipeline twice the requests and showed up as ~10 % of
+//    MFMA utilisation where an operand is k-contiguous).
+//  k-strided tile: [BK k][W cols]; row = 2W bytes; the 64-byte granule g of row k is stored at granule g ^ (k & 3):
+//    the 4 rows x 64 B that half a wave fetches in one transposing read cover all banks once.
+// A k-strided tile may gather its columns from two column ranges of the matrix (`gw` > 0: tile columns in groups of
+// gw, even groups from columns c, odd groups from columns F + c): the fused gate|up product of the SwiGLU block then
+// has a gate column and its up column in the same wave's accumulators.
 // ---------------------------------------------------------------------------
-template <int W, bool KS>
-__device__ __forceinline__ uint32_t loader_src_offset(int chunk, int lane, int ld) {  // in bytes
+template <int BK, int W, bool KS>
+__device__ __forceinline__ uint32_t loader_src_offset(int chunk, int lane, int ld, int gw = 0, int F = 0) {  // in bytes
   const int pos = chunk * 1024 + lane * 16;
   if (!KS) {
-    const int r = pos >> 7, q = (pos >> 4) & 7;
-    const int p = q ^ ((r >> 1) & 7);
+    constexpr int PR = BK / 8;                 // pieces per row
+    constexpr int SH = BK == 64 ? 1 : 2;
+    const int r = pos / (2 * BK), q = (pos >> 4) & (PR - 1);
+    const int p = q ^ ((r >> SH) & (PR - 1));
     return (uint32_t)(r * ld + p * 8) * 2u;
   } else {
     constexpr int RB = W * 2;
     const int k = pos / RB, q = (pos % RB) >> 4;
     const int p = q ^ ((k & 3) << 2);
-    return (uint32_t)(k * ld + p * 8) * 2u;
+    int col = p * 8;
+    if (gw > 0) col = ((col / gw) & 1) * F + (col / (2 * gw)) * gw + col % gw;
+    return (uint32_t)(k * ld + col) * 2u;
   }
 }
 
-// a W x 64 (or 64 x W) tile is W/8 chunks of 1 KB; wave w moves chunks w, w + NW, ...
-template <int W, int NW>
+// a W x BK (or BK x W) tile is W * BK / 512 chunks of 1 KB; wave w moves chunks w, w + NW, ...
+template <int BK, int W, int NW>
 __device__ __forceinline__ void issue_tile_loads(const char* __restrict__ g, const uint32_t* off, char* __restrict__ lds, int wave) {
 #pragma unroll
-  for (int i = 0; i < W / 8 / NW; i++) load16_to_lds(g + off[i], lds + (wave + NW * i) * 1024);
+  for (int i = 0; i < W * BK / 512 / NW; i++) load16_to_lds(g + off[i], lds + (wave + NW * i) * 1024);
 }
 
-// fragment (8 k-values for row/col = lane % 32 of a 32-wide block) for k-step ks (0..3)
-template <int W, bool KS>
+// fragment (8 k-values for row/col = lane % 32 of a 32-wide block) for k-step ks (16 k each)
+template <int BK, int W, bool KS>
 __device__ __forceinline__ bf16x8 read_frag(const char* __restrict__ lds, int base, int blk, int ks, int lane) {
   if (!KS) {
+    constexpr int PR = BK / 8;
+    constexpr int SH = BK == 64 ? 1 : 2;
     const int r = base + blk * 32 + (lane & 31);
     const int p = ks * 2 + (lane >> 5);
-    const int q = p ^ ((r >> 1) & 7);
-    return *(const bf16x8*)(lds + r * 128 + q * 16);
+    const int q = p ^ ((r >> SH) & (PR - 1));
+    return *(const bf16x8*)(lds + r * (2 * BK) + q * 16);
   } else {
     constexpr int RB = W * 2;
     const int k = ks * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
@@ -85,15 +89,15 @@ __device__ __forceinline__ bf16x8 read_frag(const char* __restrict__ lds, int ba
 }
 
 // Fragments of one 16-wide k-step for the wave's sub-tile.
-template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+template <int BK, int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
 struct Frags {
   static constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
   bf16x8 a[TM], b[TN];
   __device__ __forceinline__ void load(const char* __restrict__ cA, const char* __restrict__ cB, int ks, int wm, int wn, int lane) {
 #pragma unroll
-    for (int t = 0; t < TM; t++) a[t] = read_frag<BM, AKS>(cA, wm * (BM / WGM), t, ks, lane);
+    for (int t = 0; t < TM; t++) a[t] = read_frag<BK, BM, AKS>(cA, wm * (BM / WGM), t, ks, lane);
 #pragma unroll
-    for (int t = 0; t < TN; t++) b[t] = read_frag<BN, BKS>(cB, wn * (BN / WGN), t, ks, lane);
+    for (int t = 0; t < TN; t++) b[t] = read_frag<BK, BN, BKS>(cB, wn * (BN / WGN), t, ks, lane);
   }
 };
 
@@ -114,8 +118,8 @@ __device__ __forceinline__ void interleave() {
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
-__device__ __forceinline__ void mma_step(const Frags<BM, BN, WGM, WGN, AKS, BKS>& f, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
+template <int BK, int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
+__device__ __forceinline__ void mma_step(const Frags<BK, BM, BN, WGM, WGN, AKS, BKS>& f, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
 #pragma unroll
   for (int tm = 0; tm < TM; tm++)
@@ -123,6 +127,10 @@ __device__ __forceinline__ void mma_step(const Frags<BM, BN, WGM, WGN, AKS, BKS>
     for (int tn = 0; tn < TN; tn++)
       acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[tn], f.a[tm], acc[tm][tn], 0, 0, 0);
 }
+
+namespace k64 {
+constexpr int BK = 64;  // k-extent of one operand tile in LDS (128 bytes per row of a k-contiguous operand: whole cache lines)
+constexpr int NB = 5;   // operand tiles in the LDS ring (A and B tiles alternate): 2.5 k-blocks of 64
 
 // The pipeline.  Operand tiles of 64 k are numbered A_0, B_0, A_1, B_1, ...; tile n lives in ring buffer n % 5.
 // A k-block (A_j, B_j) is four k-steps of 16; fragments are double-buffered in registers (f0, f1), the fragments
@@ -145,18 +153,18 @@ constexpr bool b_first() { return !AKS; }
 // of k-block j+1.
 template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
 __device__ __forceinline__ void half_even(const char* gS, const uint32_t* offS, char* __restrict__ fill, const char* __restrict__ cA,
-                                          const char* __restrict__ cB, Frags<BM, BN, WGM, WGN, AKS, BKS>& f0,
-                                          Frags<BM, BN, WGM, WGN, AKS, BKS>& f1, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32],
+                                          const char* __restrict__ cB, Frags<BK, BM, BN, WGM, WGN, AKS, BKS>& f0,
+                                          Frags<BK, BM, BN, WGM, WGN, AKS, BKS>& f1, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32],
                                           int wave, int wm, int wn, int lane) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
   constexpr int NR = TM * (AKS ? 2 : 1) + TN * (BKS ? 2 : 1), NM = TM * TN;
   constexpr int WS = b_first<AKS>() ? BM : BN;  // the odd tiles are A tiles when B goes first
-  issue_tile_loads<WS, NW>(gS, offS, fill, wave);
+  issue_tile_loads<BK, WS, NW>(gS, offS, fill, wave);
   f1.load(cA, cB, 1, wm, wn, lane);
-  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
+  mma_step<BK, BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
   interleave<0, NM, NR, WS / 8 / NW>();
   f0.load(cA, cB, 2, wm, wn, lane);
-  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
+  mma_step<BK, BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
   interleave<0, NM, NR, 0>();
 }
 
@@ -165,19 +173,19 @@ __device__ __forceinline__ void half_even(const char* gS, const uint32_t* offS, 
 template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
 __device__ __forceinline__ void half_odd(const char* gF, const uint32_t* offF, char* __restrict__ fill, const char* __restrict__ cA,
                                          const char* __restrict__ cB, const char* __restrict__ nA, const char* __restrict__ nB,
-                                         Frags<BM, BN, WGM, WGN, AKS, BKS>& f0, Frags<BM, BN, WGM, WGN, AKS, BKS>& f1,
+                                         Frags<BK, BM, BN, WGM, WGN, AKS, BKS>& f0, Frags<BK, BM, BN, WGM, WGN, AKS, BKS>& f1,
                                          f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], int wave, int wm, int wn, int lane) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
   constexpr int NR = TM * (AKS ? 2 : 1) + TN * (BKS ? 2 : 1), NM = TM * TN;
   constexpr int WF = b_first<AKS>() ? BN : BM;
-  issue_tile_loads<WF, NW>(gF, offF, fill, wave);
+  issue_tile_loads<BK, WF, NW>(gF, offF, fill, wave);
   f1.load(cA, cB, 3, wm, wn, lane);
-  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
+  mma_step<BK, BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
   interleave<0, NM, NR, WF / 8 / NW>();
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(WF / 8 / NW));
   __builtin_amdgcn_s_barrier();
   f0.load(nA, nB, 0, wm, wn, lane);
-  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
+  mma_step<BK, BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
   interleave<0, NM, NR, 0>();
 }
 
@@ -186,96 +194,6 @@ __device__ __forceinline__ void half_odd(const char* gF, const uint32_t* offF, c
 namespace k32 {
 constexpr int BK = 32;  // k-extent of one LDS stage (64 bytes of bf16)
 constexpr int NS = 4;   // stages in the LDS ring: loads run 3 stages ahead of the MFMAs
-
-// ---------------------------------------------------------------------------
-// LDS layouts (all permutations are of 16-byte pieces, the unit of the loader)
-//  k-contiguous tile: [rows][32 k]; row = 64 B = 4 pieces; piece p of row r is
-//    stored at piece p ^ ((r >> 2) & 3): 16 consecutive rows hit 16 distinct
-//    16-byte bank groups for the fragment reads.
-//  k-strided tile: [32 k][W cols]; row = 2W bytes; the 64-byte granule g of row
-//    k is stored at granule g ^ (k & 3): the 4 rows x 64 B that half a wave
-//    fetches in one transposing read cover all banks once.
-// ---------------------------------------------------------------------------
-template <int W, bool KS>
-__device__ __forceinline__ uint32_t loader_src_offset(int chunk, int lane, int ld) {  // in bytes
-  const int pos = chunk * 1024 + lane * 16;
-  if (!KS) {
-    const int r = pos >> 6, q = (pos >> 4) & 3;
-    const int p = q ^ ((r >> 2) & 3);
-    return (uint32_t)(r * ld + p * 8) * 2u;
-  } else {
-    constexpr int RB = W * 2;
-    const int k = pos / RB, q = (pos % RB) >> 4;
-    const int p = q ^ ((k & 3) << 2);
-    return (uint32_t)(k * ld + p * 8) * 2u;
-  }
-}
-
-// a W x 32 (or 32 x W) tile is W/16 chunks of 1 KB; wave w moves chunks w, w + NW, ...
-template <int W, int NW>
-__device__ __forceinline__ void issue_tile_loads(const char* __restrict__ g, const uint32_t* off, char* __restrict__ lds, int wave) {
-#pragma unroll
-  for (int i = 0; i < W / 16 / NW; i++) load16_to_lds(g + off[i], lds + (wave + NW * i) * 1024);
-}
-
-// fragment (8 k-values for row/col = lane % 32 of a 32-wide block) for k-step ks (0 or 1)
-template <int W, bool KS>
-__device__ __forceinline__ bf16x8 read_frag(const char* __restrict__ lds, int base, int blk, int ks, int lane) {
-  if (!KS) {
-    const int r = base + blk * 32 + (lane & 31);
-    const int p = ks * 2 + (lane >> 5);
-    const int q = p ^ ((r >> 2) & 3);
-    return *(const bf16x8*)(lds + r * 64 + q * 16);
-  } else {
-    constexpr int RB = W * 2;
-    const int k = ks * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
-    const int c = base + blk * 32 + ((lane >> 4) & 1) * 16 + 4 * (lane & 3);
-    const int a0 = k * RB + ((((c >> 5) ^ (k & 3))) << 6) + ((c * 2) & 63);
-    bf16x4 lo = lds_read_tr4(lds + a0);
-    bf16x4 hi = lds_read_tr4(lds + a0 + 4 * RB);
-    return cat4(lo, hi);
-  }
-}
-
-// Fragments of one 16-wide k-step for the wave's sub-tile.
-template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
-struct Frags {
-  static constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
-  bf16x8 a[TM], b[TN];
-  __device__ __forceinline__ void load(const char* __restrict__ cA, const char* __restrict__ cB, int ks, int wm, int wn, int lane) {
-#pragma unroll
-    for (int t = 0; t < TM; t++) a[t] = read_frag<BM, AKS>(cA, wm * (BM / WGM), t, ks, lane);
-#pragma unroll
-    for (int t = 0; t < TN; t++) b[t] = read_frag<BN, BKS>(cB, wn * (BN / WGN), t, ks, lane);
-  }
-};
-
-// Scheduling hint for one k-step: between consecutive MFMAs (NM of them) place
-// the NV global->LDS loads and the NR LDS reads issued for later steps, the LDS
-// reads within the first three quarters so their latency is covered by the rest.
-// Masks: 0x020 = vector memory read, 0x100 = LDS read, 0x008 = MFMA.
-template <int I, int NM, int NR, int NV>
-__device__ __forceinline__ void interleave() {
-  if constexpr (I < NM) {
-    constexpr int SPAN = NM * 3 / 4 > 0 ? NM * 3 / 4 : 1;
-    constexpr int v = (I + 1) * NV / NM - I * NV / NM;
-    constexpr int r = I < SPAN ? (I + 1) * NR / SPAN - I * NR / SPAN : 0;
-    if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
-    if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    interleave<I + 1, NM, NR, NV>();
-  }
-}
-
-template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
-__device__ __forceinline__ void mma_step(const Frags<BM, BN, WGM, WGN, AKS, BKS>& f, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32]) {
-  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
-#pragma unroll
-  for (int tm = 0; tm < TM; tm++)
-#pragma unroll
-    for (int tn = 0; tn < TN; tn++)
-      acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[tn], f.a[tm], acc[tm][tn], 0, 0, 0);
-}
 
 // One stage (32 of k) of the pipeline.  On entry f0 holds the fragments of
 // k-step 0 of the current stage (cA, cB).  Starts the loads of the stage three
@@ -289,20 +207,20 @@ template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS>
 __device__ __forceinline__ void ring_step(const char* gA, const char* gB, const uint32_t* offA, const uint32_t* offB,
                                           char* __restrict__ fA, char* __restrict__ fB, const char* __restrict__ cA,
                                           const char* __restrict__ cB, const char* __restrict__ nA, const char* __restrict__ nB,
-                                          Frags<BM, BN, WGM, WGN, AKS, BKS>& f0, Frags<BM, BN, WGM, WGN, AKS, BKS>& f1,
+                                          Frags<BK, BM, BN, WGM, WGN, AKS, BKS>& f0, Frags<BK, BM, BN, WGM, WGN, AKS, BKS>& f1,
                                           f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], int wave, int wm, int wn, int lane) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
   constexpr int NR = TM * (AKS ? 2 : 1) + TN * (BKS ? 2 : 1), NM = TM * TN;
   constexpr int LPS = (BM + BN) / 16 / NW;  // loads per stage per wave
-  issue_tile_loads<BM, NW>(gA, offA, fA, wave);
-  issue_tile_loads<BN, NW>(gB, offB, fB, wave);
+  issue_tile_loads<BK, BM, NW>(gA, offA, fA, wave);
+  issue_tile_loads<BK, BN, NW>(gB, offB, fB, wave);
   f1.load(cA, cB, 1, wm, wn, lane);
-  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
+  mma_step<BK, BM, BN, WGM, WGN, AKS, BKS>(f0, acc);
   interleave<0, NM, NR, LPS>();
   __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
   __builtin_amdgcn_s_barrier();
   f0.load(nA, nB, 0, wm, wn, lane);
-  mma_step<BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
+  mma_step<BK, BM, BN, WGM, WGN, AKS, BKS>(f1, acc);
   interleave<0, NM, NR, 0>();
 }
 
@@ -312,6 +230,11 @@ template <int BM, int BN, int WGM, int WGN, bool AKS, bool BKS, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32, NW = WGM * WGN;
   constexpr bool K32 = AKS && BKS;  // which pipeline
+  // EPI_SWIGLU: the B tile gathers GW gate columns and their GW up columns per wave (see loader_src_offset); the
+  // launch runs over N = 2 F tile columns that stand for F logical ones.
+  constexpr bool SWIGLU = EPI == EPI_SWIGLU;
+  constexpr int GW = SWIGLU ? BN / WGN / 2 : 0;
+  static_assert(!SWIGLU || (!AKS && BKS), "the fused SwiGLU epilogue belongs to the forward layout");
   constexpr int BUF = (BM > BN ? BM : BN) * 128;        // k64: one ring buffer holds an A or a B tile
   constexpr int RING = K32 ? k32::NS * (BM + BN) * 64 : k64::NB * BUF;
   // the epilogue reuses the ring as staging space
@@ -337,7 +260,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   const int n0 = (in_group / gsize) * BN;
 
   const char* gA = (const char*)((const bf16*)g.A + (AKS ? (size_t)m0 : (size_t)m0 * g.lda));
-  const char* gB = (const char*)((const bf16*)g.B + (BKS ? (size_t)n0 : (size_t)n0 * g.ldb));
+  const char* gB = (const char*)((const bf16*)g.B + (BKS ? (size_t)(SWIGLU ? n0 / 2 : n0) : (size_t)n0 * g.ldb));
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; i++)
@@ -362,9 +285,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     const size_t stepB = (size_t)BK * g.ldb * 2;
     uint32_t offA[BM / 16 / NW], offB[BN / 16 / NW];
 #pragma unroll
-    for (int i = 0; i < BM / 16 / NW; i++) offA[i] = loader_src_offset<BM, AKS>(wave + NW * i, lane, g.lda);
+    for (int i = 0; i < BM / 16 / NW; i++) offA[i] = loader_src_offset<BK, BM, AKS>(wave + NW * i, lane, g.lda);
 #pragma unroll
-    for (int i = 0; i < BN / 16 / NW; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
+    for (int i = 0; i < BN / 16 / NW; i++) offB[i] = loader_src_offset<BK, BN, BKS>(wave + NW * i, lane, g.ldb, GW, g.swiglu_F);
     // nk is a multiple of 4 (K is a multiple of 128).  Stage t lives in ring slot t % 4.
     const int nk = g.K / BK, last = nk - 1;
     // The k axis may be cut into pieces that live in different buffers (kernels.h): the outer loop runs over the
@@ -374,16 +297,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     // choice is a scalar select, so the inner loop stays one basic block.
     const int nseg = g.n_seg > 0 ? g.n_seg : 1;
     const int seg_stages = nk / nseg;
-    issue_tile_loads<BM, NW>(gA, offA, sA0, wave);
-    issue_tile_loads<BN, NW>(gB, offB, sB0, wave);
-    issue_tile_loads<BM, NW>(gA + stepA, offA, sA1, wave);
-    issue_tile_loads<BN, NW>(gB + stepB, offB, sB1, wave);
-    issue_tile_loads<BM, NW>(gA + 2 * stepA, offA, sA2, wave);
-    issue_tile_loads<BN, NW>(gB + 2 * stepB, offB, sB2, wave);
+    issue_tile_loads<BK, BM, NW>(gA, offA, sA0, wave);
+    issue_tile_loads<BK, BN, NW>(gB, offB, sB0, wave);
+    issue_tile_loads<BK, BM, NW>(gA + stepA, offA, sA1, wave);
+    issue_tile_loads<BK, BN, NW>(gB + stepB, offB, sB1, wave);
+    issue_tile_loads<BK, BM, NW>(gA + 2 * stepA, offA, sA2, wave);
+    issue_tile_loads<BK, BN, NW>(gB + 2 * stepB, offB, sB2, wave);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPS));
     __builtin_amdgcn_s_barrier();
 
-    Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
+    Frags<BK, BM, BN, WGM, WGN, AKS, BKS> f0, f1;
     f0.load(sA0, sB0, 0, wm, wn, lane);
     const char *curA = gA, *curB = gB;
     for (int sg = 0; sg < nseg; sg++) {
@@ -412,9 +335,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 
     uint32_t offA[LA], offB[LB];
 #pragma unroll
-    for (int i = 0; i < LA; i++) offA[i] = loader_src_offset<BM, AKS>(wave + NW * i, lane, g.lda);
+    for (int i = 0; i < LA; i++) offA[i] = loader_src_offset<BK, BM, AKS>(wave + NW * i, lane, g.lda);
 #pragma unroll
-    for (int i = 0; i < LB; i++) offB[i] = loader_src_offset<BN, BKS>(wave + NW * i, lane, g.ldb);
+    for (int i = 0; i < LB; i++) offB[i] = loader_src_offset<BK, BN, BKS>(wave + NW * i, lane, g.ldb, GW, g.swiglu_F);
 
     // K is a multiple of 128: an even number of k-blocks.  Past the end the last k-block is fetched again into
     // dead buffers, which keeps the number of loads in flight uniform for the counted wait.
@@ -434,13 +357,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     constexpr bool PIECES = AKS && BKS;
     const int nseg = (PIECES && g.n_seg > 0) ? g.n_seg : 1;
     const int seg_blocks = np / nseg;
-    issue_tile_loads<WF, NW>(gF, offF, ring, wave);                                            // F_0 -> buffer 0
-    issue_tile_loads<WS, NW>(gS, offS, ring + BUF, wave);                                      // S_0 -> buffer 1
-    issue_tile_loads<WF, NW>(gF + (size_t)min(1, lastp) * stepF, offF, ring + 2 * BUF, wave);  // F_1 -> buffer 2
+    issue_tile_loads<BK, WF, NW>(gF, offF, ring, wave);                                            // F_0 -> buffer 0
+    issue_tile_loads<BK, WS, NW>(gS, offS, ring + BUF, wave);                                      // S_0 -> buffer 1
+    issue_tile_loads<BK, WF, NW>(gF + (size_t)min(1, lastp) * stepF, offF, ring + 2 * BUF, wave);  // F_1 -> buffer 2
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(WF / 8 / NW));
     __builtin_amdgcn_s_barrier();
 
-    Frags<BM, BN, WGM, WGN, AKS, BKS> f0, f1;
+    Frags<BK, BM, BN, WGM, WGN, AKS, BKS> f0, f1;
     f0.load(ring + (BF ? BUF : 0), ring + (BF ? 0 : BUF), 0, wm, wn, lane);
     int jf = 0, js = 1;  // buffers of F_j and S_j
     const char *curF = gF, *curS = gS;
@@ -487,12 +410,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   char* strip = ring + wave * (32 * ROWB);
   const bf16* bias = (const bf16*)g.bias;
   const bf16* aux = (const bf16*)g.aux;
-  const bool has_bias = (EPI == EPI_BF16 || EPI == EPI_GELU || EPI == EPI_RESID) && bias != nullptr;
+  constexpr bool RESID = EPI == EPI_RESID || EPI == EPI_RESID_F32 || EPI == EPI_RESID_F32_OUT16;
+  constexpr bool AUX_F32 = EPI == EPI_RESID_F32 || EPI == EPI_RESID_F32_OUT16;   // the residual is read in fp32
+  constexpr bool OUT_F32 = EPI == EPI_F32_ACC || EPI == EPI_F32_SET || EPI == EPI_RESID_F32;
+  const bool has_bias = (EPI == EPI_BF16 || EPI == EPI_GELU || RESID) && bias != nullptr;
   constexpr int PPR = WN / 8;                       // 8-column pieces per strip row
   constexpr int NIT = 32 * PPR / 64;                // pieces per lane per strip
   static_assert(64 % PPR == 0, "a lane keeps its column piece across iterations");
   const int cp = lane % PPR, row0 = lane / PPR;     // piece it*64 + lane -> row row0 + it * (64 / PPR)
-  const int n = n0 + wn * WN + cp * 8;
+  // output column of the lane's piece.  SwiGLU: the first half of the wave's strip row holds GW gate columns, the
+  // second half their up columns; both go to u[:, 2F] (gate at column c, up at F + c), their product to C2[:, F].
+  const bool up_piece = SWIGLU && cp >= PPR / 2;
+  const int nlog = SWIGLU ? n0 / 2 + wn * GW + (up_piece ? cp - PPR / 2 : cp) * 8 : 0;   // logical column of the piece
+  const int n = SWIGLU ? (up_piece ? g.swiglu_F + nlog : nlog) : n0 + wn * WN + cp * 8;
   float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (has_bias) {
     const bf16x8 b = *(const bf16x8*)(bias + n);
@@ -511,10 +441,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int it = 0; it < NIT; it++) ax[it] = *(const bf16x8*)(aux + (size_t)(mbase + it * (64 / PPR)) * g.ld_aux + n);
     }
-    if (EPI == EPI_F32_ACC) {
+    if (EPI == EPI_F32_ACC || AUX_F32) {
 #pragma unroll
       for (int it = 0; it < NIT; it++) {
-        const float* cptr = (const float*)g.C + (size_t)(mbase + it * (64 / PPR)) * g.ldc + n;
+        const float* cptr = (AUX_F32 ? (const float*)g.aux : (const float*)g.C) + (size_t)(mbase + it * (64 / PPR)) * (AUX_F32 ? g.ld_aux : g.ldc) + n;
         old0[it] = *(const f32x4*)cptr;
         old1[it] = *(const f32x4*)(cptr + 4);
       }
@@ -536,9 +466,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
       const f32x4 hi = *(const f32x4*)(strip + row * ROWB + cp * 32 + 16);
       float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       const size_t m = (size_t)(mbase + it * (64 / PPR));
-      if (EPI == EPI_F32_ACC || EPI == EPI_F32_SET) {
+      if (OUT_F32) {
         float* cptr = (float*)g.C + m * g.ldc + n;
-        if (EPI == EPI_F32_ACC) {
+        if (EPI == EPI_F32_ACC || EPI == EPI_RESID_F32) {
+          if (EPI == EPI_RESID_F32) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) v[i] += bv[i];
+          }
 #pragma unroll
           for (int i = 0; i < 4; i++) { v[i] += old0[it][i]; v[4 + i] += old1[it][i]; }
         }
@@ -550,6 +484,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
         if (EPI == EPI_RESID) {
 #pragma unroll
           for (int i = 0; i < 8; i++) v[i] += bf2f(ax[it][i]);
+        }
+        if (EPI == EPI_RESID_F32_OUT16) {
+#pragma unroll
+          for (int i = 0; i < 4; i++) { v[i] += old0[it][i]; v[4 + i] += old1[it][i]; }
         }
         if (EPI == EPI_GELU_BWD) {
 #pragma unroll
@@ -568,6 +506,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
           for (int i = 0; i < 8; i++) o2[i] = f2bf(gelu_f(v[i]));
           *(bf16x8*)((bf16*)g.C2 + m * g.ldc + n) = o2;
+        }
+        if (SWIGLU && !up_piece) {
+          // silu(gate) * up from the fp32 accumulators: the up piece sits PPR / 2 pieces further in the strip row
+          const f32x4 ulo = *(const f32x4*)(strip + row * ROWB + (cp + PPR / 2) * 32);
+          const f32x4 uhi = *(const f32x4*)(strip + row * ROWB + (cp + PPR / 2) * 32 + 16);
+          const float up[8] = {ulo[0], ulo[1], ulo[2], ulo[3], uhi[0], uhi[1], uhi[2], uhi[3]};
+          bf16x8 o2;
+#pragma unroll
+          for (int i = 0; i < 8; i++) o2[i] = f2bf(silu_f(v[i]) * up[i]);
+          *(bf16x8*)((bf16*)g.C2 + m * g.ldc2 + nlog) = o2;
         }
       }
     }
@@ -718,6 +666,9 @@ hipError_t dispatch(GemmLayout layout, GemmEpilogue epi, int t, const GemmArgs& 
     if (epi == EPI_BF16) return run_tile<false, true, EPI_BF16>(t, a, s);
     if (epi == EPI_GELU) return run_tile<false, true, EPI_GELU>(t, a, s);
     if (epi == EPI_RESID) return run_tile<false, true, EPI_RESID>(t, a, s);
+    if (epi == EPI_RESID_F32) return run_tile<false, true, EPI_RESID_F32>(t, a, s);
+    if (epi == EPI_RESID_F32_OUT16) return run_tile<false, true, EPI_RESID_F32_OUT16>(t, a, s);
+    if (epi == EPI_SWIGLU) return run_tile<false, true, EPI_SWIGLU>(t, a, s);
   } else if (layout == GEMM_NT) {
     if (epi == EPI_BF16) return run_tile<false, false, EPI_BF16>(t, a, s);
     if (epi == EPI_GELU_BWD) return run_tile<false, false, EPI_GELU_BWD>(t, a, s);
@@ -728,14 +679,21 @@ hipError_t dispatch(GemmLayout layout, GemmEpilogue epi, int t, const GemmArgs& 
 }
 
 // the same problem restricted to output columns [c0, c0 + n)
-GemmArgs column_range(GemmLayout layout, const GemmArgs& a, int c0, int n) {
+GemmArgs column_range(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, int c0, int n) {
   GemmArgs b = a;
   b.N = n;
-  const bool f32 = layout == GEMM_TN;
+  if (epi == EPI_SWIGLU) {  // c0 tile columns stand for c0 / 2 logical ones of each of gate, up and the product
+    b.B = (const bf16*)a.B + c0 / 2;
+    b.C = (bf16*)a.C + c0 / 2;
+    b.C2 = (bf16*)a.C2 + c0 / 2;
+    return b;
+  }
+  const bool f32 = layout == GEMM_TN || epi == EPI_RESID_F32;
+  const bool aux_f32 = epi == EPI_RESID_F32 || epi == EPI_RESID_F32_OUT16;
   b.C = f32 ? (void*)((float*)a.C + c0) : (void*)((bf16*)a.C + c0);
   if (a.C2) b.C2 = (bf16*)a.C2 + c0;
   if (a.bias) b.bias = (const bf16*)a.bias + c0;
-  if (a.aux) b.aux = (const bf16*)a.aux + c0;
+  if (a.aux) b.aux = aux_f32 ? (const void*)((const float*)a.aux + c0) : (const void*)((const bf16*)a.aux + c0);
   if (a.colsum_part) b.colsum_part = a.colsum_part + c0;
   if (layout == GEMM_NT) {
     b.B = (const bf16*)a.B + (size_t)c0 * a.ldb;  // B is [N, K]
@@ -764,9 +722,9 @@ hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a_in
   const Plan p = cached_plan(a.M, a.N, layout == GEMM_TN);
   if (p.tile[0] < 0) return hipErrorInvalidValue;
   if (p.parts == 1) return dispatch(layout, epi, p.tile[0], a, s);
-  hipError_t e = dispatch(layout, epi, p.tile[0], column_range(layout, a, 0, p.n0), s);
+  hipError_t e = dispatch(layout, epi, p.tile[0], column_range(layout, epi, a, 0, p.n0), s);
   if (e != hipSuccess) return e;
-  return dispatch(layout, epi, p.tile[1], column_range(layout, a, p.n0, a.N - p.n0), s);
+  return dispatch(layout, epi, p.tile[1], column_range(layout, epi, a, p.n0, a.N - p.n0), s);
 }
 
 }  // namespace ah

@@ -12,7 +12,13 @@ enum GemmEpilogue {
   EPI_RESID = 2,     // C = acc (+ bias[n]) + aux[m, n]
   EPI_GELU_BWD = 3,  // C = acc * gelu'(aux[m, n])
   EPI_F32_ACC = 4,   // C (fp32) = beta * C + acc  (callers use this one; beta selects the kernel)
-  EPI_F32_SET = 5    // C (fp32) = acc            (internal: EPI_F32_ACC with beta == 0)
+  EPI_F32_SET = 5,   // C (fp32) = acc            (internal: EPI_F32_ACC with beta == 0)
+  EPI_RESID_F32 = 6,        // C (fp32) = acc (+ bias[n]) + aux[m, n] (fp32): the residual stream kept in fp32
+  EPI_RESID_F32_OUT16 = 7,  // C (bf16) = acc (+ bias[n]) + aux[m, n] (fp32): the last layer's output
+  // NN only, B = [K, 2F] holding gate | up: the launch's N is 2F, every tile pairs gate columns with their up
+  // columns; C[M, 2F] (ldc) = gate | up as bf16 (kept for backward), C2[M, F] (ldc2) = silu(gate) * up taken from
+  // the fp32 accumulators.  No bias.  F = swiglu_F, a multiple of 128.
+  EPI_SWIGLU = 8
 };
 
 constexpr int kMaxGemmSegments = 16;
@@ -25,6 +31,7 @@ struct GemmArgs {
   const void* bias;  // [N] bf16 or NULL
   const void* aux;   // [M, N] bf16 (residual, or the pre-activation for EPI_GELU_BWD)
   int lda, ldb, ldc, ld_aux;
+  int ldc2, swiglu_F;  // EPI_SWIGLU only
   int M, N, K;
   int beta;
   int group, xcd_remap;  // tile rasterisation (set by launch_gemm)
@@ -53,12 +60,13 @@ hipError_t launch_attention_bwd(const void* qkv, const void* o, const float* lse
 
 // ---- row-wise / element-wise kernels (bf16 I/O, fp32 math) ----
 // a = norm(x) * gamma (+ beta); stats[2*T] = (mean, rstd) per row (RMS: mean slot unused = 0)
+// x_f32: x is fp32 (the residual stream kept in fp32) instead of bf16
 hipError_t launch_norm_fwd(bool rms, const void* x, const void* gamma, const void* beta, void* a, float* stats,
-                           int T, int h, float eps, hipStream_t s);
+                           int T, int h, float eps, hipStream_t s, bool x_f32 = false);
 // dx = dres + norm_bwd(da);  partial column sums of (da*xhat, da, dres) go to `part` ([3][nblk][h] fp32),
 // written, or with acc != 0 added to what is there (a group of micro-batches sharing one set of partial sums)
 hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float* stats, const void* gamma,
-                           const void* dres, void* dx, float* part, int T, int h, hipStream_t s, int acc = 0);
+                           const void* dres, void* dx, float* part, int T, int h, hipStream_t s, int acc = 0, bool x_f32 = false);
 int norm_bwd_blocks(int T);
 // g[c] = beta * g[c] + sum_b part[b][c]
 hipError_t launch_colsum_finish(const float* part, int nblk, int n, float* g, int beta, hipStream_t s);
@@ -71,6 +79,8 @@ int colsum_blocks(int T);
 hipError_t launch_rope(void* qkv, const float* cos_sin, int T, int S, int nh, int d, float sign, hipStream_t s);
 // device-to-device copy of a multiple of 16 bytes
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+// n bf16 values (a multiple of 8) -> fp32
+hipError_t launch_widen(void* dst_f32, const void* src_bf16, size_t n, hipStream_t s);
 // m = silu(gu[:, :F]) * gu[:, F:]
 hipError_t launch_swiglu_fwd(const void* gu, void* m, int T, int F, hipStream_t s);
 // dgu from dm and gu

@@ -34,23 +34,39 @@ __device__ __forceinline__ void block_sum2(float& a, float& b, float* red) {
   b = red[4] + red[5] + red[6] + red[7];
 }
 
+// Eight consecutive values of a tensor of the residual stream, which is bf16 or (residual_fp32) fp32.
+template <bool F32> struct XVec;
+template <> struct XVec<false> {
+  bf16x8 v;
+  __device__ __forceinline__ void load(const void* base, size_t elem) { v = *(const bf16x8*)((const bf16*)base + elem); }
+  __device__ __forceinline__ float get(int j) const { return bf2f(v[j]); }
+};
+template <> struct XVec<true> {
+  f32x4 a, b;
+  __device__ __forceinline__ void load(const void* base, size_t elem) {
+    a = *(const f32x4*)((const float*)base + elem);
+    b = *(const f32x4*)((const float*)base + elem + 4);
+  }
+  __device__ __forceinline__ float get(int j) const { return j < 4 ? a[j] : b[j - 4]; }
+};
+
 // ---------------------------------------------------------------- norm forward: one block per row
-template <bool RMS, int MAXC>
-__global__ __launch_bounds__(NT) void norm_fwd_kernel(const bf16* __restrict__ x, const bf16* __restrict__ gamma,
+template <bool RMS, int MAXC, bool XF32>
+__global__ __launch_bounds__(NT) void norm_fwd_kernel(const void* __restrict__ x, const bf16* __restrict__ gamma,
                                                       const bf16* __restrict__ beta, bf16* __restrict__ a,
                                                       float* __restrict__ stats, int h, float eps) {
   __shared__ float red[8];
   const int row = blockIdx.x, nchunk = h >> 3;
-  const bf16* xr = x + (size_t)row * h;
   float v[MAXC][8];
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXC; i++) {
     const int c = threadIdx.x + i * NT;
     if (c < nchunk) {
-      bf16x8 t = *(const bf16x8*)(xr + c * 8);
+      XVec<XF32> t;
+      t.load(x, (size_t)row * h + c * 8);
 #pragma unroll
-      for (int j = 0; j < 8; j++) { v[i][j] = bf2f(t[j]); s += RMS ? v[i][j] * v[i][j] : v[i][j]; }
+      for (int j = 0; j < 8; j++) { v[i][j] = t.get(j); s += RMS ? v[i][j] * v[i][j] : v[i][j]; }
     }
   }
   float mean = 0.f, rstd;
@@ -93,8 +109,8 @@ __global__ __launch_bounds__(NT) void norm_fwd_kernel(const bf16* __restrict__ x
 // reduced, so that memory latency, the block reduction and the arithmetic overlap.
 constexpr int NTB = 512;  // threads per block of the norm backward; MAXC here = ceil(hidden / 4096)
 
-template <bool RMS, int MAXC>
-__global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ da, const bf16* __restrict__ x,
+template <bool RMS, int MAXC, bool XF32>
+__global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ da, const void* __restrict__ x,
                                                        const float* __restrict__ stats, const bf16* __restrict__ gamma,
                                                        const bf16* __restrict__ dres, bf16* __restrict__ dx,
                                                        float* __restrict__ part, int T, int h, int rpb, int acc) {
@@ -119,8 +135,10 @@ __global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ 
   }
   // the block's rows are j * nblk + blockIdx.x for j in [r0, r1)
   const int r0 = 0, r1 = (T - (int)blockIdx.x + nblk - 1) / nblk;
-  bf16x8 tx[RB][MAXC], td[RB][MAXC], tr[RB][MAXC];   // current batch
-  bf16x8 nx[PIPE ? RB : 1][PIPE ? MAXC : 1], nd[PIPE ? RB : 1][PIPE ? MAXC : 1], nr[PIPE ? RB : 1][PIPE ? MAXC : 1];  // next batch
+  XVec<XF32> tx[RB][MAXC];
+  bf16x8 td[RB][MAXC], tr[RB][MAXC];   // current batch
+  XVec<XF32> nx[PIPE ? RB : 1][PIPE ? MAXC : 1];
+  bf16x8 nd[PIPE ? RB : 1][PIPE ? MAXC : 1], nr[PIPE ? RB : 1][PIPE ? MAXC : 1];  // next batch
   float mean[RB], rstd[RB], nmean[PIPE ? RB : 1], nrstd[PIPE ? RB : 1];
   // a short last batch repeats its last row; the copies are computed but neither summed nor stored
   auto fetch = [&](int rb, auto& fx, auto& fd, auto& fr, auto& fm, auto& fs) {
@@ -131,7 +149,7 @@ __global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ 
       for (int i = 0; i < MAXC; i++) {
         const int c = threadIdx.x + i * NTB;
         if (c < nchunk) {
-          fx[k][i] = *(const bf16x8*)(x + (size_t)row * h + c * 8);
+          fx[k][i].load(x, (size_t)row * h + c * 8);
           fd[k][i] = *(const bf16x8*)(da + (size_t)row * h + c * 8);
           fr[k][i] = *(const bf16x8*)(dres + (size_t)row * h + c * 8);
         }
@@ -160,7 +178,7 @@ __global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ 
 #pragma unroll
           for (int j = 0; j < 8; j++) {
             const float d = bf2f(td[k][i][j]);
-            const float xh = __builtin_fmaf(bf2f(tx[k][i][j]), rstd[k], nm);
+            const float xh = __builtin_fmaf(tx[k][i].get(j), rstd[k], nm);
             const float w = d * bf2f(gam[i][j]);
             sw += w;
             swx = __builtin_fmaf(w, xh, swx);
@@ -194,7 +212,7 @@ __global__ __launch_bounds__(NTB) void norm_bwd_kernel(const bf16* __restrict__ 
 #pragma unroll
           for (int j = 0; j < 8; j++) {
             const float r = bf2f(tr[k][i][j]);
-            const float xh = __builtin_fmaf(bf2f(tx[k][i][j]), rstd[k], nm);
+            const float xh = __builtin_fmaf(tx[k][i].get(j), rstd[k], nm);
             const float w = bf2f(td[k][i][j]) * bf2f(gam[i][j]);
             s_r[i][j] += r;
             o[j] = f2bf(r + rstd[k] * (w - c1 - xh * c2));
@@ -322,6 +340,15 @@ __global__ __launch_bounds__(NT) void copy16_kernel(const uint4* __restrict__ sr
   if (i < n16) dst[i] = src[i];
 }
 
+// bf16 -> fp32, 8 elements per lane (the stage input entering an fp32 residual stream)
+__global__ __launch_bounds__(NT) void widen_kernel(const bf16* __restrict__ src, float* __restrict__ dst, size_t n8) {
+  const size_t i = (size_t)blockIdx.x * NT + threadIdx.x;
+  if (i >= n8) return;
+  const bf16x8 t = *(const bf16x8*)(src + i * 8);
+  *(f32x4*)(dst + i * 8) = f32x4{bf2f(t[0]), bf2f(t[1]), bf2f(t[2]), bf2f(t[3])};
+  *(f32x4*)(dst + i * 8 + 4) = f32x4{bf2f(t[4]), bf2f(t[5]), bf2f(t[6]), bf2f(t[7])};
+}
+
 // ---------------------------------------------------------------- SwiGLU
 __global__ __launch_bounds__(NT) void swiglu_fwd_kernel(const bf16* __restrict__ gu, bf16* __restrict__ m, long n8, int F) {
   const long idx = (long)blockIdx.x * NT + threadIdx.x;
@@ -362,17 +389,23 @@ __global__ __launch_bounds__(NT) void swiglu_bwd_kernel(const bf16* __restrict__
 
 namespace {
 template <bool RMS, int MAXC>
-void norm_fwd_go(const void* x, const void* gamma, const void* beta, void* a, float* stats, int T, int h, float eps, hipStream_t s) {
-  hipLaunchKernelGGL((norm_fwd_kernel<RMS, MAXC>), dim3(T), dim3(NT), 0, s, (const bf16*)x, (const bf16*)gamma, (const bf16*)beta,
-                     (bf16*)a, stats, h, eps);
+void norm_fwd_go(const void* x, bool x_f32, const void* gamma, const void* beta, void* a, float* stats, int T, int h, float eps, hipStream_t s) {
+  if (x_f32)
+    hipLaunchKernelGGL((norm_fwd_kernel<RMS, MAXC, true>), dim3(T), dim3(NT), 0, s, x, (const bf16*)gamma, (const bf16*)beta, (bf16*)a, stats, h, eps);
+  else
+    hipLaunchKernelGGL((norm_fwd_kernel<RMS, MAXC, false>), dim3(T), dim3(NT), 0, s, x, (const bf16*)gamma, (const bf16*)beta, (bf16*)a, stats, h, eps);
 }
 template <bool RMS, int MAXC>
-void norm_bwd_go(const void* da, const void* x, const float* stats, const void* gamma, const void* dres, void* dx, float* part,
+void norm_bwd_go(const void* da, const void* x, bool x_f32, const float* stats, const void* gamma, const void* dres, void* dx, float* part,
                  int T, int h, int acc, hipStream_t s) {
   const int nblk = norm_bwd_blocks(T);
   const int rpb = (T + nblk - 1) / nblk;
-  hipLaunchKernelGGL((norm_bwd_kernel<RMS, MAXC>), dim3(nblk), dim3(NTB), 0, s, (const bf16*)da, (const bf16*)x, stats,
-                     (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, part, T, h, rpb, acc);
+  if (x_f32)
+    hipLaunchKernelGGL((norm_bwd_kernel<RMS, MAXC, true>), dim3(nblk), dim3(NTB), 0, s, (const bf16*)da, x, stats,
+                       (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, part, T, h, rpb, acc);
+  else
+    hipLaunchKernelGGL((norm_bwd_kernel<RMS, MAXC, false>), dim3(nblk), dim3(NTB), 0, s, (const bf16*)da, x, stats,
+                       (const bf16*)gamma, (const bf16*)dres, (bf16*)dx, part, T, h, rpb, acc);
 }
 }  // namespace
 
@@ -393,23 +426,23 @@ int norm_bwd_blocks(int T) {
   } while (0)
 
 hipError_t launch_norm_fwd(bool rms, const void* x, const void* gamma, const void* beta, void* a, float* stats, int T,
-                           int h, float eps, hipStream_t s) {
+                           int h, float eps, hipStream_t s, bool x_f32) {
   if (h % 8 || h > 16384) return hipErrorInvalidValue;
-  if (rms) AH_BY_CHUNKS(norm_fwd_go, true, x, gamma, beta, a, stats, T, h, eps, s);
-  else AH_BY_CHUNKS(norm_fwd_go, false, x, gamma, beta, a, stats, T, h, eps, s);
+  if (rms) AH_BY_CHUNKS(norm_fwd_go, true, x, x_f32, gamma, beta, a, stats, T, h, eps, s);
+  else AH_BY_CHUNKS(norm_fwd_go, false, x, x_f32, gamma, beta, a, stats, T, h, eps, s);
   return hipGetLastError();
 }
 
 #define AH_BWD_BY_CHUNKS(RMS)                                                                        \
   do {                                                                                               \
     const int nc = (h + 4095) / 4096;                                                                \
-    if (nc <= 1) norm_bwd_go<RMS, 1>(da, x, stats, gamma, dres, dx, part, T, h, acc, s);             \
-    else if (nc == 2) norm_bwd_go<RMS, 2>(da, x, stats, gamma, dres, dx, part, T, h, acc, s);        \
-    else norm_bwd_go<RMS, 4>(da, x, stats, gamma, dres, dx, part, T, h, acc, s);                     \
+    if (nc <= 1) norm_bwd_go<RMS, 1>(da, x, x_f32, stats, gamma, dres, dx, part, T, h, acc, s);      \
+    else if (nc == 2) norm_bwd_go<RMS, 2>(da, x, x_f32, stats, gamma, dres, dx, part, T, h, acc, s); \
+    else norm_bwd_go<RMS, 4>(da, x, x_f32, stats, gamma, dres, dx, part, T, h, acc, s);              \
   } while (0)
 
 hipError_t launch_norm_bwd(bool rms, const void* da, const void* x, const float* stats, const void* gamma, const void* dres,
-                           void* dx, float* part, int T, int h, hipStream_t s, int acc) {
+                           void* dx, float* part, int T, int h, hipStream_t s, int acc, bool x_f32) {
   if (h % 8 || h > 16384) return hipErrorInvalidValue;
   if (rms) AH_BWD_BY_CHUNKS(true);
   else AH_BWD_BY_CHUNKS(false);
@@ -446,6 +479,13 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s) 
   if (bytes % 16) return hipErrorInvalidValue;
   const size_t n16 = bytes / 16;
   hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)((n16 + NT - 1) / NT)), dim3(NT), 0, s, (const uint4*)src, (uint4*)dst, n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_widen(void* dst_f32, const void* src_bf16, size_t n, hipStream_t s) {
+  if (n % 8) return hipErrorInvalidValue;
+  const size_t n8 = n / 8;
+  hipLaunchKernelGGL(widen_kernel, dim3((unsigned)((n8 + NT - 1) / NT)), dim3(NT), 0, s, (const bf16*)src_bf16, (float*)dst_f32, n8);
   return hipGetLastError();
 }
 

@@ -44,7 +44,7 @@ struct ah_stage {
   ah_stage_config_t cfg;
   ah_stage_buffers_t bufs;
   int T, h, nh, d, hl, F, L;
-  bool llama, causal, recompute;
+  bool llama, causal, recompute, res32;
   float eps, rope_base;
   ParamEntry ptab[AH_P_COUNT];
   uint64_t layer_elems;
@@ -91,6 +91,7 @@ int validate(const ah_stage_config_t* c) {
   if (c->n_microbatches < 1) return set_error(AH_EINVAL, "n_microbatches must be >= 1");
   if (c->max_in_flight < 1 || c->max_in_flight > 4096) return set_error(AH_EINVAL, "max_in_flight %d out of range [1, 4096]", c->max_in_flight);
   if (c->recompute != 0 && c->recompute != 1) return set_error(AH_EINVAL, "recompute must be 0 or 1");
+  if (c->residual_fp32 != 0 && c->residual_fp32 != 1) return set_error(AH_EINVAL, "residual_fp32 must be 0 or 1");
   if (c->wgrad_group < 0 || c->wgrad_group > kMaxGemmSegments) return set_error(AH_EINVAL, "wgrad_group %d out of range [0, %d]", c->wgrad_group, kMaxGemmSegments);
   if (c->wgrad_group > 1 && c->recompute) return set_error(AH_EINVAL, "wgrad_group > 1 keeps activations for the deferred products: recompute must be 0");
   if (c->wgrad_group > c->max_in_flight) return set_error(AH_EINVAL, "wgrad_group %d needs max_in_flight >= %d (a slot stays occupied until its group's weight gradients are taken)", c->wgrad_group, c->wgrad_group);
@@ -117,6 +118,7 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
   s->llama = c->arch == AH_ARCH_LLAMA;
   s->causal = c->arch != AH_ARCH_BERT;
   s->recompute = c->recompute != 0;
+  s->res32 = c->residual_fp32 != 0;
   s->group = c->wgrad_group > 1 ? c->wgrad_group : 1;
   {
     // A deferred product runs at the end of its group with a k axis G times as long.  That pays for the outputs
@@ -160,13 +162,14 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o += align256(bytes); return r; };
   ActLayout& a = s->act;
-  a.x_in = take(T * h * 2);
+  const size_t rsz = s->res32 ? 4 : 2;  // bytes per element of the residual stream
+  a.x_in = take(T * h * rsz);
   const size_t keep_only_input = o;
   a.a = take(T * h * 2);
   a.qkv = take(T * 3 * hl * 2);
   a.o = take(T * hl * 2);
   a.lse = take(T * s->nh * 4);
-  a.x_mid = take(T * h * 2);
+  a.x_mid = take(T * h * rsz);
   a.c = take(T * h * 2);
   a.u = take(T * Fu * 2);
   a.g = take(T * F * 2);
@@ -406,22 +409,30 @@ hipError_t wgrad(ah_stage* s, int site, int layer, WgradWhich which, const Wgrad
 
 // One layer forward.  y == nullptr: stop after the activations backward needs
 // (used when a layer is re-run inside backward).
-hipError_t layer_forward(ah_stage* s, int layer, const ActPtrs& a, void* y, hipStream_t st) {
+hipError_t layer_forward(ah_stage* s, int layer, const ActPtrs& a, void* y, bool y_is_stage_output, hipStream_t st) {
   const LayerPtrs p = layer_ptrs(s, layer);
   const int T = s->T, h = s->h, hl = s->hl, F = s->F, B = s->cfg.microbatch_size, S = s->cfg.seq_len;
-  TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_in, p.ln1_g, p.ln1_b, a.a, (float*)a.stats1, T, h, s->eps, st));
+  // the residual stream (x_in, x_mid, the next layer's x_in) is bf16 or fp32; the stage's output y is always bf16
+  const bool r32 = s->res32;
+  const GemmEpilogue resid = r32 ? EPI_RESID_F32 : EPI_RESID;
+  const GemmEpilogue resid_out = r32 ? (y_is_stage_output ? EPI_RESID_F32_OUT16 : EPI_RESID_F32) : EPI_RESID;
+  TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_in, p.ln1_g, p.ln1_b, a.a, (float*)a.stats1, T, h, s->eps, st, r32));
   TRY(gemm(s, SITE_QKV_FWD, GEMM_NN, EPI_BF16, a.a, h, p.wqkv, 3 * hl, a.qkv, 3 * hl, T, 3 * hl, h, p.bqkv, nullptr, 0, nullptr, 0, st));
   if (s->llama) TIMED(SITE_ROPE, launch_rope(a.qkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, 1.f, st));
   TIMED(SITE_ATTN_FWD, launch_attention_fwd(a.qkv, a.o, (float*)a.lse, B, S, s->nh, s->d, s->causal, st));
-  TRY(gemm(s, SITE_WO_FWD, GEMM_NN, EPI_RESID, a.o, hl, p.wo, h, a.x_mid, h, T, h, hl, p.bo, a.x_in, h, nullptr, 0, st));
-  TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_mid, p.ln2_g, p.ln2_b, a.c, (float*)a.stats2, T, h, s->eps, st));
+  TRY(gemm(s, SITE_WO_FWD, GEMM_NN, resid, a.o, hl, p.wo, h, a.x_mid, h, T, h, hl, p.bo, a.x_in, h, nullptr, 0, st));
+  TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_mid, p.ln2_g, p.ln2_b, a.c, (float*)a.stats2, T, h, s->eps, st, r32));
   if (!s->llama) {
     TRY(gemm(s, SITE_FC1_FWD, GEMM_NN, EPI_GELU, a.c, h, p.w1, F, a.u, F, T, F, h, p.b1, nullptr, 0, a.g, 0, st));
   } else {
-    TRY(gemm(s, SITE_FC1_FWD, GEMM_NN, EPI_BF16, a.c, h, p.w1, 2 * F, a.u, 2 * F, T, 2 * F, h, nullptr, nullptr, 0, nullptr, 0, st));
-    TIMED(SITE_SWIGLU_FWD, launch_swiglu_fwd(a.u, a.g, T, F, st));
+    // gate | up product with silu(gate) * up taken in its epilogue from the fp32 accumulators (u = gate | up is kept for backward)
+    GemmArgs g = {};
+    g.A = a.c; g.B = p.w1; g.C = a.u; g.C2 = a.g;
+    g.lda = h; g.ldb = 2 * F; g.ldc = 2 * F; g.ldc2 = F; g.swiglu_F = F; g.M = T; g.N = 2 * F; g.K = h;
+    SiteTimer t(s, SITE_FC1_FWD, st);
+    TRY(launch_gemm(GEMM_NN, EPI_SWIGLU, g, st));
   }
-  if (y) TRY(gemm(s, SITE_FC2_FWD, GEMM_NN, EPI_RESID, a.g, F, p.w2, h, y, h, T, h, F, p.b2, a.x_mid, h, nullptr, 0, st));
+  if (y) TRY(gemm(s, SITE_FC2_FWD, GEMM_NN, resid_out, a.g, F, p.w2, h, y, h, T, h, F, p.b2, a.x_mid, h, nullptr, 0, st));
   return hipSuccess;
 }
 
@@ -481,7 +492,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   const bool du_reused = sd != st && dqkv == du;
   if (du_reused) TRY(hipEventRecord(ev[2], sd));
   // second norm backward; dx_mid = dy + norm_bwd(dc); column sums give d(gain), d(offset), d(b2)
-  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part_n2, T, h, st, vp.acc));
+  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_mid, (const float*)a.stats2, p.ln2_g, dy, dmid, part_n2, T, h, st, vp.acc, s->res32));
   TRY(stream_order(st, sd, ev[3]));
   if (vp.finish) {
     if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n2, nb, h, p.g_ln2_g, beta, sd));
@@ -502,7 +513,7 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
   TRY(wgrad(s, SITE_QKV_WGRAD, layer, WG_QKV, wp, a.a, dqkv, p.g_wqkv, h, 3 * hl, st, sd));
   TRY(gemm(s, SITE_QKV_DGRAD, GEMM_NT, EPI_BF16, dqkv, 3 * hl, p.wqkv, 3 * hl, dsm, h, T, h, 3 * hl, nullptr, nullptr, 0, nullptr, 0, st));  // da
   // first norm backward; dx = dx_mid + norm_bwd(da); column sums give d(gain), d(offset), d(bo)
-  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part_n1, T, h, st, vp.acc));
+  TIMED(SITE_NORM_BWD, launch_norm_bwd(rms, dsm, a.x_in, (const float*)a.stats1, p.ln1_g, dmid, dx, part_n1, T, h, st, vp.acc, s->res32));
   TRY(stream_order(st, sd, ev[5]));
   if (vp.finish) {
     if (rms) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_n1, nb, h, p.g_ln1_g, beta, sd));
@@ -539,13 +550,13 @@ hipError_t ensure_rope(ah_stage* s, hipStream_t st) {
 
 hipError_t stage_forward(ah_stage* s, int slot, const void* x, void* y, hipStream_t st, hipEvent_t* ev) {
   TRY(ensure_rope(s, st));
-  const size_t xbytes = (size_t)s->T * s->h * 2;
-  TRY(launch_copy(act_ptrs(s, slot, 0).x_in, x, xbytes, st));
+  if (s->res32) TRY(launch_widen(act_ptrs(s, slot, 0).x_in, x, (size_t)s->T * s->h, st));
+  else TRY(launch_copy(act_ptrs(s, slot, 0).x_in, x, (size_t)s->T * s->h * 2, st));
   if (ev) TRY(hipEventRecord(ev[0], st));
   for (int l = 0; l < s->L; l++) {
     const ActPtrs a = act_ptrs(s, slot, l);
     void* out = (l + 1 < s->L) ? (void*)act_ptrs(s, slot, l + 1).x_in : y;
-    TRY(layer_forward(s, l, a, out, st));
+    TRY(layer_forward(s, l, a, out, l + 1 == s->L, st));
     if (ev) TRY(hipEventRecord(ev[l + 1], st));
   }
   return hipSuccess;
@@ -625,7 +636,7 @@ hipError_t stage_backward(ah_stage* s, int slot, const void* dy, void* dx, hipSt
   if (ev) TRY(hipEventRecord(ev[s->L], st));
   for (int l = s->L - 1; l >= 0; l--) {
     const ActPtrs a = act_ptrs(s, slot, l);
-    if (s->recompute) TRY(layer_forward(s, l, a, nullptr, st));
+    if (s->recompute) TRY(layer_forward(s, l, a, nullptr, false, st));
     BwdBufs bb = {wsb + s->ws.dmid, wsb + s->ws.dbig, wsb + s->ws.dbig};
     void* out = (l == 0) ? dx : (void*)(wsb + ((l & 1) ? s->ws.d1 : s->ws.d0));
     if (deferred) {

@@ -18,7 +18,7 @@ def profile_layers(w, n_layers, warmup=2, iters=5, max_in_flight=1):
     import paper_2512_20953_amd as P
     cfg = P.StageConfig.make(arch=w["arch"], n_layers=n_layers, hidden=w["hidden"], n_heads=w["n_heads"],
                              head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
-                             max_in_flight=max_in_flight, recompute=w["recompute"])
+                             max_in_flight=max_in_flight, recompute=w["recompute"], residual_fp32=w.get("res32", 0))
     st = P.Stage(cfg)
     st.params.normal_(0.0, 0.02)
     rep = st.profile(warmup=warmup, iters=iters)

@@ -22,7 +22,8 @@ WORKLOADS = {
     "gpt1p3b":   dict(arch="gpt",   n_layers=4,  hidden=2048, n_heads=16, head_dim=128, ffn=8192,  seq=2048, mb=1, n_mb=8,  tp=1, recompute=0),
     "gpt7b_tp2": dict(arch="gpt",   n_layers=4,  hidden=4096, n_heads=32, head_dim=128, ffn=16384, seq=2048, mb=2, n_mb=8,  tp=2, recompute=0),
     "gpt13b":    dict(arch="gpt",   n_layers=10, hidden=5120, n_heads=40, head_dim=128, ffn=20480, seq=2048, mb=1, n_mb=16, tp=1, recompute=0),
-    "llama7b":   dict(arch="llama", n_layers=8,  hidden=4096, n_heads=32, head_dim=128, ffn=11008, seq=4096, mb=1, n_mb=8,  tp=1, recompute=1),
+    # res32: the stage carries its residual stream in fp32 (8 layers of this block miss the gradient tolerance otherwise)
+    "llama7b":   dict(arch="llama", n_layers=8,  hidden=4096, n_heads=32, head_dim=128, ffn=11008, seq=4096, mb=1, n_mb=8,  tp=1, recompute=1, res32=1),
     # bidirectional-attention stages (the BERT-Large shape: 24 layers of h 1024, 16 heads x 64, FFN 4096, S 512; 6 of them here)
     "bert_tiny": dict(arch="bert",  n_layers=2,  hidden=256,  n_heads=4,  head_dim=64,  ffn=1024,  seq=256,  mb=2, n_mb=2,  tp=1, recompute=0),
     "bert_large": dict(arch="bert", n_layers=6,  hidden=1024, n_heads=16, head_dim=64,  ffn=4096,  seq=512,  mb=8, n_mb=8,  tp=1, recompute=0),

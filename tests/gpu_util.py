@@ -90,12 +90,12 @@ def error_views(got, ref, tile=None):
     return out
 
 
-def make_cfgs(w, max_in_flight=1, recompute=None, wgrad_group=0):
+def make_cfgs(w, max_in_flight=1, recompute=None, wgrad_group=0, res32=None):
     nh, hl, Fl = SI.local_dims(w)
     gcfg = P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
                               head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
                               max_in_flight=max(max_in_flight, wgrad_group), recompute=w["recompute"] if recompute is None else recompute,
-                              wgrad_group=wgrad_group)
+                              wgrad_group=wgrad_group, residual_fp32=w.get("res32", 0) if res32 is None else res32)
     ocfg = R.StageCfg(w["arch"], w["n_layers"], w["hidden"], nh, w["head_dim"], Fl, w["seq"],
                       1e-6 if w["arch"] == "llama" else 1e-5, 10000.0)
     return gcfg, ocfg

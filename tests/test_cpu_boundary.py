@@ -28,7 +28,7 @@ def _cfg(name, **kw):
     w = dict(SI.WORKLOADS[name], **kw)
     return P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
                               head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
-                              max_in_flight=w.get("max_in_flight", 1), recompute=w["recompute"])
+                              max_in_flight=w.get("max_in_flight", 1), recompute=w["recompute"], residual_fp32=w.get("res32", 0))
 
 
 @pytest.mark.parametrize("name", list(SI.WORKLOADS))
@@ -49,11 +49,17 @@ def test_all_workloads_are_supported_and_sized(name):
     assert s1["activation_bytes_per_layer_per_slot"] == s["activation_bytes_per_layer_per_slot"]
     assert s1["workspace_bytes"] == s["workspace_bytes"]
     T = w["mb"] * w["seq"]
+    r = 2 * w.get("res32", 0)   # extra bytes per element of the two residual-stream tensors when they are fp32
     if w["recompute"]:
-        assert s["activation_bytes_per_layer_per_slot"] == 2 * T * h
+        assert s["activation_bytes_per_layer_per_slot"] == (2 + r) * T * h
     else:
-        saved = 2 * T * (4 * h + 4 * hl + 2 * F) + 4 * T * nh + 16 * T   # bf16 tensors + lse + two (mean, rstd) pairs
+        saved = 2 * T * (4 * h + 4 * hl + 2 * F) + 2 * r * T * h + 4 * T * nh + 16 * T   # bf16 tensors + lse + two (mean, rstd) pairs
         assert s["activation_bytes_per_layer_per_slot"] == saved
+    # the fp32 residual stream costs exactly 2 bytes more per element of the layer input and of x + attention block
+    s32 = query_sizes(_cfg(name, res32=1))
+    s16 = query_sizes(_cfg(name, res32=0))
+    extra = (2 if w["recompute"] else 4) * T * h
+    assert s32["activation_bytes_per_layer_per_slot"] - s16["activation_bytes_per_layer_per_slot"] == extra
 
 
 def test_known_sizes_of_the_benchmark_workload():

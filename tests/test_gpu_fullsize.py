@@ -69,6 +69,35 @@ def test_gemm_at_benchmark_shapes_sampled_entries(layout, M, N, K):
         assert U.rel_l2(U.to_np(C)[np.ix_(rows, cols)], ref0) <= tol
 
 
+@pytest.mark.parametrize("M,F,K", [
+    (4096, 4096, 1024),   # 512 tiles of 256 x 256: a wave pairs 64 gate columns with their 64 up columns
+    (2048, 2048, 512),    # 256 x 128 tiles: 32 + 32 columns per wave
+    (4096, 3072, 512),    # 6144 tile columns: two launches over column ranges with different tile shapes
+    (384, 640, 128),      # 128 x 128 tiles, odd multiples
+])
+def test_gemm_with_fused_swiglu_sampled_entries(M, F, K):
+    """gate | up product and silu(gate) * up from its epilogue, against float64 on sampled rows (all columns)."""
+    rng = np.random.default_rng(9)
+    A, W = _bf16_normal(rng, (M, K), 1.0), _bf16_normal(rng, (K, 2 * F), 0.05)
+    U_ = torch.full((M, 2 * F), float("nan"), dtype=torch.bfloat16, device="cuda")
+    Mo = torch.full((M, F), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P.gemm_nn_swiglu(U.to_dev(A), U.to_dev(W), U_, Mo)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([rng.choice(M, 40, replace=False), [0, 31, 32, 127, 128, 255, M - 1]]))
+    ref_u = A[rows].astype(np.float64) @ W.astype(np.float64)
+    ref_m = R.silu(ref_u[:, :F]) * ref_u[:, F:]
+    got_u, got_m = U.to_np(U_)[rows], U.to_np(Mo)[rows]
+    assert np.isfinite(U.to_np(U_)).all() and np.isfinite(U.to_np(Mo)).all()    # every element was written
+    eu, em = U.error_views(got_u, ref_u), U.error_views(got_m, ref_m)
+    assert eu["l2"] <= 3e-3 and eu["rows"] <= 3e-3 and eu["maxabs"] <= 4e-3, eu    # one bf16 rounding of an fp32 sum
+    assert em["l2"] <= 3e-3 and em["rows"] <= 3e-3 and em["maxabs"] <= 4e-3, em
+    # per column block of 64 (the unit the tiles gather), so that a mispaired block cannot hide in the norm
+    for c0 in range(0, F, 64):
+        assert U.rel_l2(got_m[:, c0:c0 + 64], ref_m[:, c0:c0 + 64]) <= 5e-3, c0
+        assert U.rel_l2(got_u[:, c0:c0 + 64], ref_u[:, c0:c0 + 64]) <= 5e-3, c0
+        assert U.rel_l2(got_u[:, F + c0:F + c0 + 64], ref_u[:, F + c0:F + c0 + 64]) <= 5e-3, c0
+
+
 @pytest.mark.parametrize("B,S,nh,d,causal", [(2, 2048, 16, 128, True), (1, 4096, 32, 128, True), (8, 512, 16, 64, False),
                                               (1, 2048, 4, 128, False),
                                               # launches of at most 256 blocks of 128 queries take the 64-query kernels

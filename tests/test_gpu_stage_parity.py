@@ -58,6 +58,10 @@ REDUCED = {
     "gpt_widest": dict(arch="gpt", n_layers=1, hidden=16384, n_heads=2, head_dim=128, ffn=256, seq=128, mb=1, n_mb=2, tp=1, recompute=0),
     "llama_wide": dict(arch="llama", n_layers=1, hidden=12288, n_heads=2, head_dim=64, ffn=128, seq=128, mb=2, n_mb=1, tp=1, recompute=0),
     "llama_odd": dict(arch="llama", n_layers=1, hidden=384, n_heads=6, head_dim=64, ffn=640, seq=384, mb=1, n_mb=3, tp=1, recompute=1),
+    # the residual stream carried in fp32 inside the stage: both block types, stored and recomputed activations, three layers
+    "gpt_res32": dict(arch="gpt", n_layers=3, hidden=384, n_heads=4, head_dim=128, ffn=1536, seq=256, mb=2, n_mb=2, tp=2, recompute=0, res32=1),
+    "llama_res32": dict(arch="llama", n_layers=3, hidden=512, n_heads=4, head_dim=128, ffn=768, seq=256, mb=1, n_mb=2, tp=1, recompute=0, res32=1),
+    "llama_res32_recompute": dict(arch="llama", n_layers=2, hidden=384, n_heads=6, head_dim=64, ffn=640, seq=384, mb=1, n_mb=2, tp=1, recompute=1, res32=1),
 }
 
 
@@ -66,7 +70,7 @@ def test_reduced_stages(name):
     _run_case(REDUCED[name])
 
 
-@pytest.mark.parametrize("name", ["tiny", "llama_small"])
+@pytest.mark.parametrize("name", ["tiny", "llama_small", "llama_res32"])
 def test_recompute_is_bit_identical(name):
     w = SI.WORKLOADS[name] if name in SI.WORKLOADS else REDUCED[name]
     outs = []
