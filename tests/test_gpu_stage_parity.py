@@ -376,3 +376,57 @@ def test_capture_with_deferred_gradients_is_refused():
         st.backward(0, x, y, s)      # outside a capture the same call works
         st.flush_grads(s)
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("arch", ["gpt", "llama"])
+def test_shard_outputs_sum_to_the_unsharded_block_on_gpu(arch):
+    """Section II-B on the device: with the first matrix of a block cut by columns and the second by rows, the
+    two shards' outputs are the addends of the unsharded block's output.  A one-layer stage exposes one block at
+    a time: with the second MLP matrix zero y = x + o Wo + bo (the attention block), with the out-projection zero
+    y = x + g W2 + b2 (the MLP block).  Both tensor-parallel ranks run through the C ABI on their own shard; their
+    addends are summed and compared with the unsharded stage's addend and with the oracle's partial sums."""
+    from oracle import stage_ref as R
+    tp = 2
+    w = dict(arch=arch, n_layers=1, hidden=384, n_heads=4, head_dim=128, ffn=1536, seq=256, mb=2, n_mb=1, tp=tp, recompute=0)
+    w_full = dict(w, tp=1)
+    x = SI.draw_activation(w, "x", 0)
+    second, out_proj = ("w2", "wo") if arch == "gpt" else ("wd", "wo")
+    post_bias = {"w2": "b2", "wd": None, "wo": "bo"}
+
+    def run(wl, params):
+        gcfg, _ = U.make_cfgs(wl)
+        st = P.Stage(gcfg)
+        U.load_params(st, [params])
+        xd = U.to_dev(x)
+        y = torch.empty_like(xd)
+        st.forward(0, xd, y)
+        dx = torch.empty_like(xd)
+        st.backward(0, xd, dx)       # frees the slot
+        torch.cuda.synchronize()
+        return U.to_np(y)
+
+    for zeroed, block in ((second, "attention"), (out_proj, "mlp")):
+        def prep(p):
+            p = dict(p)
+            p[zeroed] = np.zeros_like(p[zeroed])
+            for b in ("b2", "bo"):
+                if b in p and post_bias[zeroed] == b:
+                    p[b] = np.zeros_like(p[b])
+            return p
+        kept_bias = "bo" if block == "attention" else "b2"
+        full = prep(SI.draw_layer_params(w_full, 0, perturb_vectors=True))
+        bias = full[kept_bias].astype(np.float64) if kept_bias in full else 0.0
+        addend_full = run(w_full, full) - x - bias
+        shards = [prep(SI.draw_layer_params(w, 0, tp_rank=r, perturb_vectors=True)) for r in range(tp)]
+        addends = [run(w, s) - x - bias for s in shards]
+        # y is rounded to bf16 at |x + addend| ~ 1, so each recovered addend carries ~2^-9 absolute error
+        noise = 2.0 ** -9 * np.sqrt(np.mean((x + addend_full) ** 2)) / np.sqrt(np.mean(addend_full ** 2))
+        assert U.rel_l2(sum(addends), addend_full) <= 4 * noise + 1e-2, block
+        # and each shard's addend against the oracle's partial sum for that shard
+        nh, hl, Fl = SI.local_dims(w)
+        ocfg = R.StageCfg(arch, 1, w["hidden"], nh, w["head_dim"], Fl, w["seq"], 1e-6 if arch == "llama" else 1e-5)
+        for r, s in enumerate(shards):
+            s64 = {k: v.astype(np.float64) for k, v in s.items()}
+            ref = R.attn_block_partial(ocfg, s64, x.astype(np.float64)) if block == "attention" else R.mlp_block_partial(ocfg, s64, x.astype(np.float64))
+            assert U.rel_l2(addends[r], ref) <= 4 * noise + 1e-2, (block, r)
+        assert U.rel_l2(addends[0], addend_full) > 0.3    # one shard alone is not the block
