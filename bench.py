@@ -80,6 +80,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--trace-steps", type=int, default=2)
     ap.add_argument("--no-ungrouped", action="store_true", help="skip the comparison run with wgrad_group 1")
+    ap.add_argument("--overlap", type=int, default=0,
+                    help="1: forward of micro-batch m+1 is enqueued on a second stream beside backward of micro-batch m (they are "
+                         "independent; needs wgrad_group slots >= 2)")
     ap.add_argument("--no-side-stream", action="store_true",
                     help="keep all of backward on one stream, as the per-site trace does: kernel durations in a profile are then "
                          "those of kernels that own the chip (the timed figure is ~1 %% lower)")
@@ -119,11 +122,31 @@ def main():
     y, dx = torch.empty_like(xs[0]), torch.empty_like(xs[0])
     stream = torch.cuda.current_stream()
 
+    overlap = bool(args.overlap) and G >= 2
+    if overlap:
+        fstream = torch.cuda.Stream()
+        fdone = [torch.cuda.Event() for _ in range(K)]
+        ys2 = [torch.empty_like(xs[0]) for _ in range(2)]
+        step_end = torch.cuda.Event()
+
     def step():
         st.zero_grads(stream)
-        for m in range(K):
-            st.forward(m % G, xs[m], y, stream)
-            st.backward(m % G, dys[m], dx, stream)
+        if not overlap:
+            for m in range(K):
+                st.forward(m % G, xs[m], y, stream)
+                st.backward(m % G, dys[m], dx, stream)
+        else:
+            # the forward passes run ahead on their own stream: F(m+1) beside B(m); B(m) waits for F(m)
+            step_end.record(stream)
+            fstream.wait_event(step_end)          # the slots were freed by the previous step's work on `stream`
+            st.forward(0, xs[0], ys2[0], fstream)
+            fdone[0].record(fstream)
+            for m in range(K):
+                if m + 1 < K:
+                    st.forward((m + 1) % G, xs[m + 1], ys2[(m + 1) % 2], fstream)
+                    fdone[m + 1].record(fstream)
+                stream.wait_event(fdone[m])
+                st.backward(m % G, dys[m], dx, stream)
         st.flush_grads(stream)   # an incomplete last group (K not a multiple of G); otherwise nothing is pending
 
     for _ in range(args.warmup):
@@ -239,7 +262,7 @@ def main():
            "config": {"workload": args.workload, "arch": w["arch"], "layers": w["n_layers"], "hidden": w["hidden"],
                       "local_heads": w["n_heads"] // w["tp"], "head_dim": w["head_dim"], "local_ffn": w["ffn"] // w["tp"],
                       "seq_len": w["seq"], "microbatch": w["mb"], "microbatches": K, "tokens_per_step": tokens,
-                      "tp_degree": w["tp"], "recompute": w["recompute"], "residual_fp32": w.get("res32", 0), "wgrad_group": G, "parallelism": "1 GPU (one TP shard of one stage)"},
+                      "tp_degree": w["tp"], "recompute": w["recompute"], "residual_fp32": w.get("res32", 0), "wgrad_group": G, "forward_beside_backward": int(overlap), "parallelism": "1 GPU (one TP shard of one stage)"},
            "roofline": roofline, "per_microbatch_accumulation": ungrouped,
            "sites": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in s.items()} for s in sites]}
     if not args.no_cpu_baseline:

@@ -101,6 +101,78 @@ __global__ __launch_bounds__(NT) void norm_fwd_kernel(const void* __restrict__ x
   }
 }
 
+// ---------------------------------------------------------------- norm forward, rows up to 8192 wide: one wave per row
+// A wave keeps a whole row in registers (MAXI chunks of 8 values per lane), so both statistics are wave
+// reductions with no block barrier, and it walks rows w, w + (waves in the grid), ... with the next row's loads
+// issued before the current one is reduced: loads, arithmetic and stores of different rows overlap inside a wave
+// as well as across the waves of a CU.  The gain and offset stay packed in registers for all rows.
+template <bool RMS, int MAXI, bool XF32>
+__global__ __launch_bounds__(NT) void norm_fwd_wave_kernel(const void* __restrict__ x, const bf16* __restrict__ gamma,
+                                                           const bf16* __restrict__ beta, bf16* __restrict__ a,
+                                                           float* __restrict__ stats, int T, int h, float eps) {
+  const int lane = threadIdx.x & 63, nchunk = h >> 3;
+  const int nw = gridDim.x * (NT / 64);
+  int row = blockIdx.x * (NT / 64) + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const float inv_h = 1.f / h;
+  bf16x8 gam[MAXI], bet[RMS ? 1 : MAXI];
+  XVec<XF32> cur[MAXI], nxt[MAXI];
+#pragma unroll
+  for (int i = 0; i < MAXI; i++) {
+    const int c = lane + 64 * i;
+    if (c < nchunk) {
+      gam[i] = *(const bf16x8*)(gamma + c * 8);
+      if (!RMS) bet[i] = *(const bf16x8*)(beta + c * 8);
+      cur[i].load(x, (size_t)row * h + c * 8);
+    }
+  }
+  for (; row < T; row += nw) {
+    const int nr = row + nw;
+    if (nr < T) {
+#pragma unroll
+      for (int i = 0; i < MAXI; i++)
+        if (lane + 64 * i < nchunk) nxt[i].load(x, (size_t)nr * h + (lane + 64 * i) * 8);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXI; i++)
+      if (lane + 64 * i < nchunk)
+#pragma unroll
+        for (int j = 0; j < 8; j++) { const float v = cur[i].get(j); s += RMS ? v * v : v; }
+    s = wave_sum(s);
+    float mean = 0.f, rstd;
+    if (RMS) {
+      rstd = rsqrtf(s * inv_h + eps);
+    } else {
+      mean = s * inv_h;
+      float q = 0.f;
+#pragma unroll
+      for (int i = 0; i < MAXI; i++)
+        if (lane + 64 * i < nchunk)
+#pragma unroll
+          for (int j = 0; j < 8; j++) { const float d = cur[i].get(j) - mean; q += d * d; }
+      rstd = rsqrtf(wave_sum(q) * inv_h + eps);
+    }
+    if (lane == 0) { stats[2 * row] = mean; stats[2 * row + 1] = rstd; }
+#pragma unroll
+    for (int i = 0; i < MAXI; i++) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) {
+        bf16x8 o;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          float r = (cur[i].get(j) - mean) * rstd * bf2f(gam[i][j]);
+          if (!RMS) r += bf2f(bet[i][j]);
+          o[j] = f2bf(r);
+        }
+        *(bf16x8*)(a + (size_t)row * h + c * 8) = o;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < MAXI; i++) cur[i] = nxt[i];
+  }
+}
+
 // ---------------------------------------------------------------- norm backward
 // Block b handles rows b, b + nblk, b + 2*nblk, ... (so that the blocks, which advance together, read one
 // contiguous stretch of memory at a time and spread over all HBM channels); a thread keeps its columns for
@@ -388,6 +460,18 @@ __global__ __launch_bounds__(NT) void swiglu_bwd_kernel(const bf16* __restrict__
 }  // namespace
 
 namespace {
+// one wave per row; MAXI = chunks of 8 values per lane
+template <bool RMS, int MAXI>
+void norm_fwd_wave_go(const void* x, bool x_f32, const void* gamma, const void* beta, void* a, float* stats, int T, int h, float eps, hipStream_t s) {
+  // two rows per wave where the rows suffice (the second row's loads run under the first row's arithmetic), at most 8 waves per CU
+  const int waves = T >= 4096 ? 2048 : (T + 1) / 2 > 0 ? (T + 1) / 2 : 1;
+  const dim3 grid((waves + NT / 64 - 1) / (NT / 64));
+  if (x_f32)
+    hipLaunchKernelGGL((norm_fwd_wave_kernel<RMS, MAXI, true>), grid, dim3(NT), 0, s, x, (const bf16*)gamma, (const bf16*)beta, (bf16*)a, stats, T, h, eps);
+  else
+    hipLaunchKernelGGL((norm_fwd_wave_kernel<RMS, MAXI, false>), grid, dim3(NT), 0, s, x, (const bf16*)gamma, (const bf16*)beta, (bf16*)a, stats, T, h, eps);
+}
+
 template <bool RMS, int MAXC>
 void norm_fwd_go(const void* x, bool x_f32, const void* gamma, const void* beta, void* a, float* stats, int T, int h, float eps, hipStream_t s) {
   if (x_f32)
@@ -428,6 +512,23 @@ int norm_bwd_blocks(int T) {
 hipError_t launch_norm_fwd(bool rms, const void* x, const void* gamma, const void* beta, void* a, float* stats, int T,
                            int h, float eps, hipStream_t s, bool x_f32) {
   if (h % 8 || h > 16384) return hipErrorInvalidValue;
+  static int wave_rows = -1;
+  if (wave_rows < 0) wave_rows = getenv("AH_NORM_FWD_BLOCK_PER_ROW") ? 0 : 1;  // tuning aid
+  const int per_lane = (h / 8 + 63) / 64;   // chunks per lane with one wave per row
+  if (wave_rows && per_lane <= 16) {
+#define AH_WAVE_ROWS(RMS)                                                                                     \
+    do {                                                                                                      \
+      if (per_lane <= 2) norm_fwd_wave_go<RMS, 2>(x, x_f32, gamma, beta, a, stats, T, h, eps, s);             \
+      else if (per_lane <= 4) norm_fwd_wave_go<RMS, 4>(x, x_f32, gamma, beta, a, stats, T, h, eps, s);        \
+      else if (per_lane <= 8) norm_fwd_wave_go<RMS, 8>(x, x_f32, gamma, beta, a, stats, T, h, eps, s);        \
+      else if (per_lane <= 12) norm_fwd_wave_go<RMS, 12>(x, x_f32, gamma, beta, a, stats, T, h, eps, s);      \
+      else norm_fwd_wave_go<RMS, 16>(x, x_f32, gamma, beta, a, stats, T, h, eps, s);                          \
+    } while (0)
+    if (rms) AH_WAVE_ROWS(true);
+    else AH_WAVE_ROWS(false);
+#undef AH_WAVE_ROWS
+    return hipGetLastError();
+  }
   if (rms) AH_BY_CHUNKS(norm_fwd_go, true, x, x_f32, gamma, beta, a, stats, T, h, eps, s);
   else AH_BY_CHUNKS(norm_fwd_go, false, x, x_f32, gamma, beta, a, stats, T, h, eps, s);
   return hipGetLastError();
