@@ -15,6 +15,7 @@
 // columns of one output row: 8-byte bf16 or 16-byte fp32 accesses in the epilogue.
 #include "common.h"
 #include "kernels.h"
+#include <algorithm>
 #include <cstdlib>
 #include <mutex>
 #include <vector>
@@ -431,15 +432,48 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
   }
   float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // EPI_GELU_BWD: this lane's column sums over the current 64-row slab
   const bool want_colsum = EPI == EPI_GELU_BWD && g.colsum_part != nullptr;
+  // EPI_ROPE: this lane's 8 pairs, the partner piece, and (cos, sin) of 64 / PPR angle steps (the distance between a
+  // lane's consecutive rows), read once from the table's row of that position; per strip of 32 rows (which never
+  // straddles a sequence: S is a multiple of 128) the angles of the lane's first row are read from the table and
+  // carried from row to row by rotation
+  const bool rot = EPI == EPI_ROPE && n < g.rope_cols;
+  float rc[8], rs[8], dcs_c[8], dcs_s[8];
+  int rope_pcp = 0, rope_i0 = 0;
+  float rope_sgn = 0.f;
+  if (EPI == EPI_ROPE && rot) {
+    const int d = g.rope_d, ch = (cp * 8) % d, half = d >> 1;
+    const bool lower = ch < half;
+    rope_pcp = lower ? cp + (d >> 4) : cp - (d >> 4);
+    rope_i0 = lower ? ch : ch - half;
+    rope_sgn = lower ? -1.f : 1.f;
+    const float* t = g.rope_cs + ((size_t)(64 / PPR) * half + rope_i0) * 2;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; q4++) {
+      const f32x4 e = *(const f32x4*)(t + 4 * q4);
+      dcs_c[2 * q4] = e[0]; dcs_s[2 * q4] = e[1]; dcs_c[2 * q4 + 1] = e[2]; dcs_s[2 * q4 + 1] = e[3];
+    }
+  }
 #pragma unroll
   for (int tm = 0; tm < TM; tm++) {
     const int mbase = m0 + wm * WM + tm * 32 + row0;
+    if (EPI == EPI_ROPE && rot) {
+      const float* t = g.rope_cs + ((size_t)(mbase % g.rope_S) * (g.rope_d >> 1) + rope_i0) * 2;
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        const f32x4 e = *(const f32x4*)(t + 4 * q4);
+        rc[2 * q4] = e[0]; rs[2 * q4] = e[1]; rc[2 * q4 + 1] = e[2]; rs[2 * q4 + 1] = e[3];
+      }
+    }
     // operands of the epilogue that come from memory: issue their loads before the strip round trip
-    bf16x8 ax[NIT];
+    bf16x8 ax[NIT], ax2[EPI == EPI_SWIGLU_BWD ? NIT : 1];
     f32x4 old0[NIT], old1[NIT];
-    if (EPI == EPI_RESID || EPI == EPI_GELU_BWD) {
+    if (EPI == EPI_RESID || EPI == EPI_GELU_BWD || EPI == EPI_SWIGLU_BWD) {
 #pragma unroll
       for (int it = 0; it < NIT; it++) ax[it] = *(const bf16x8*)(aux + (size_t)(mbase + it * (64 / PPR)) * g.ld_aux + n);
+    }
+    if (EPI == EPI_SWIGLU_BWD) {  // aux = gate | up: the up columns sit swiglu_F further
+#pragma unroll
+      for (int it = 0; it < NIT; it++) ax2[it] = *(const bf16x8*)(aux + (size_t)(mbase + it * (64 / PPR)) * g.ld_aux + g.swiglu_F + n);
     }
     if (EPI == EPI_F32_ACC || AUX_F32) {
 #pragma unroll
@@ -485,6 +519,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
           for (int i = 0; i < 8; i++) v[i] += bf2f(ax[it][i]);
         }
+        if (EPI == EPI_ROPE && rot) {
+          // rotary embedding on the fp32 sums: the pair of column c of a head is c +- d/2, d/16 pieces away in the
+          // same strip row (a wave's strip holds whole heads: WN % d == 0, checked by the caller)
+          const f32x4 plo = *(const f32x4*)(strip + row * ROWB + rope_pcp * 32);
+          const f32x4 phi = *(const f32x4*)(strip + row * ROWB + rope_pcp * 32 + 16);
+          const float pv[8] = {plo[0], plo[1], plo[2], plo[3], phi[0], phi[1], phi[2], phi[3]};
+#pragma unroll
+          for (int i = 0; i < 8; i++) {
+            v[i] = v[i] * rc[i] + rope_sgn * pv[i] * rs[i];
+            // the lane's next row is 64 / PPR positions further: rotate (cos, sin) by that many steps of the angle
+            const float c2 = rc[i] * dcs_c[i] - rs[i] * dcs_s[i];
+            rs[i] = rs[i] * dcs_c[i] + rc[i] * dcs_s[i];
+            rc[i] = c2;
+          }
+        }
         if (EPI == EPI_RESID_F32_OUT16) {
 #pragma unroll
           for (int i = 0; i < 4; i++) { v[i] += old0[it][i]; v[4 + i] += old1[it][i]; }
@@ -494,18 +543,30 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
           for (int i = 0; i < 8; i++) v[i] *= gelu_grad_f(bf2f(ax[it][i]));
         }
         bf16x8 o;
+        if (EPI == EPI_SWIGLU_BWD) {
+          // v = dm; d(gate) = dm up silu'(gate) goes to column n, d(up) = dm silu(gate) to column F + n
+          bf16x8 o2;
 #pragma unroll
-        for (int i = 0; i < 8; i++) o[i] = f2bf(v[i]);
-        *(bf16x8*)((bf16*)g.C + m * g.ldc + n) = o;
-        if (EPI == EPI_GELU_BWD) {
+          for (int i = 0; i < 8; i++) {
+            const float x = bf2f(ax[it][i]), sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+            o[i] = f2bf(v[i] * bf2f(ax2[it][i]) * sg * __builtin_fmaf(x, 1.0f - sg, 1.0f));
+            o2[i] = f2bf(v[i] * x * sg);
+          }
+          *(bf16x8*)((bf16*)g.C + m * g.ldc + g.swiglu_F + n) = o2;
+        } else {
 #pragma unroll
-          for (int i = 0; i < 8; i++) cs[i] += bf2f(o[i]);
+          for (int i = 0; i < 8; i++) o[i] = f2bf(v[i]);
         }
+        *(bf16x8*)((bf16*)g.C + m * g.ldc + n) = o;
         if (EPI == EPI_GELU) {
           bf16x8 o2;
 #pragma unroll
           for (int i = 0; i < 8; i++) o2[i] = f2bf(gelu_f(v[i]));
           *(bf16x8*)((bf16*)g.C2 + m * g.ldc + n) = o2;
+        }
+        if (EPI == EPI_GELU_BWD) {
+#pragma unroll
+          for (int i = 0; i < 8; i++) cs[i] += bf2f(o[i]);
         }
         if (SWIGLU && !up_piece) {
           // silu(gate) * up from the fp32 accumulators: the up piece sits PPR / 2 pieces further in the strip row
@@ -653,6 +714,15 @@ hipError_t run_tile(int t, const GemmArgs& a, hipStream_t s) {
 
 }  // namespace
 
+int gemm_min_wave_cols(int M, int N, GemmLayout layout) {
+  if (!gemm_shape_ok(M, N, 128)) return 0;
+  const Plan p = cached_plan(M, N, layout == GEMM_TN);
+  if (p.tile[0] < 0) return 0;
+  int w = kTiles[p.tile[0]].bn / kTiles[p.tile[0]].wgn;
+  if (p.parts == 2) w = std::min(w, kTiles[p.tile[1]].bn / kTiles[p.tile[1]].wgn);
+  return w;
+}
+
 int gemm_tile_area(int M, int N, GemmLayout layout) {
   if (!gemm_shape_ok(M, N, 128)) return 0;
   const Plan p = cached_plan(M, N, layout == GEMM_TN);
@@ -669,9 +739,11 @@ hipError_t dispatch(GemmLayout layout, GemmEpilogue epi, int t, const GemmArgs& 
     if (epi == EPI_RESID_F32) return run_tile<false, true, EPI_RESID_F32>(t, a, s);
     if (epi == EPI_RESID_F32_OUT16) return run_tile<false, true, EPI_RESID_F32_OUT16>(t, a, s);
     if (epi == EPI_SWIGLU) return run_tile<false, true, EPI_SWIGLU>(t, a, s);
+    if (epi == EPI_ROPE) return run_tile<false, true, EPI_ROPE>(t, a, s);
   } else if (layout == GEMM_NT) {
     if (epi == EPI_BF16) return run_tile<false, false, EPI_BF16>(t, a, s);
     if (epi == EPI_GELU_BWD) return run_tile<false, false, EPI_GELU_BWD>(t, a, s);
+    if (epi == EPI_SWIGLU_BWD) return run_tile<false, false, EPI_SWIGLU_BWD>(t, a, s);
   } else if (layout == GEMM_TN) {
     if (epi == EPI_F32_ACC) return a.beta ? run_tile<true, true, EPI_F32_ACC>(t, a, s) : run_tile<true, true, EPI_F32_SET>(t, a, s);
   }
@@ -695,6 +767,7 @@ GemmArgs column_range(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, in
   if (a.bias) b.bias = (const bf16*)a.bias + c0;
   if (a.aux) b.aux = aux_f32 ? (const void*)((const float*)a.aux + c0) : (const void*)((const bf16*)a.aux + c0);
   if (a.colsum_part) b.colsum_part = a.colsum_part + c0;
+  b.rope_cols = a.rope_cols - c0;  // the rotated columns are counted from the launch's first column
   if (layout == GEMM_NT) {
     b.B = (const bf16*)a.B + (size_t)c0 * a.ldb;  // B is [N, K]
   } else {

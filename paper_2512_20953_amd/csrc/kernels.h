@@ -18,7 +18,15 @@ enum GemmEpilogue {
   // NN only, B = [K, 2F] holding gate | up: the launch's N is 2F, every tile pairs gate columns with their up
   // columns; C[M, 2F] (ldc) = gate | up as bf16 (kept for backward), C2[M, F] (ldc2) = silu(gate) * up taken from
   // the fp32 accumulators.  No bias.  F = swiglu_F, a multiple of 128.
-  EPI_SWIGLU = 8
+  EPI_SWIGLU = 8,
+  // NT only, the input gradient of the SwiGLU block's second matrix with the activation's backward fused: with
+  // dm = acc [M, F] and aux = gate | up [M, 2F] (ld_aux), C[M, 2F] (ldc) = dm up silu'(gate) | dm silu(gate).
+  // N = F = swiglu_F; dm itself is not stored.
+  EPI_SWIGLU_BWD = 9,
+  // NN only, no bias: C = acc with the rotary embedding applied to columns [0, rope_cols) on the fp32 sums (heads of
+  // rope_d columns, pairs (i, i + rope_d / 2), position = row % rope_S, table rope_cs[pos][i] = (cos, sin)).  Every
+  // tile's wave strip must hold whole heads: gemm_min_wave_cols(M, N) % rope_d == 0.
+  EPI_ROPE = 10
 };
 
 constexpr int kMaxGemmSegments = 16;
@@ -29,9 +37,11 @@ struct GemmArgs {
   void* C;           // [M, N]
   void* C2;          // EPI_GELU second output
   const void* bias;  // [N] bf16 or NULL
-  const void* aux;   // [M, N] bf16 (residual, or the pre-activation for EPI_GELU_BWD)
+  const void* aux;   // [M, N] bf16 (residual, or the pre-activation for EPI_GELU_BWD); fp32 for the _F32 residual epilogues
   int lda, ldb, ldc, ld_aux;
-  int ldc2, swiglu_F;  // EPI_SWIGLU only
+  int ldc2, swiglu_F;  // EPI_SWIGLU, EPI_SWIGLU_BWD
+  const float* rope_cs;  // EPI_ROPE only
+  int rope_S, rope_d, rope_cols;
   int M, N, K;
   int beta;
   int group, xcd_remap;  // tile rasterisation (set by launch_gemm)
@@ -49,6 +59,7 @@ struct GemmArgs {
 // M, N, K multiples of 128, all leading dimensions multiples of 8.
 hipError_t launch_gemm(GemmLayout layout, GemmEpilogue epi, const GemmArgs& a, hipStream_t s);
 bool gemm_shape_ok(int M, int N, int K);
+int gemm_min_wave_cols(int M, int N, GemmLayout layout);  // columns of a wave's sub-tile, the smallest over the launches that cover the output
 int gemm_tile_area(int M, int N, GemmLayout layout);  // rows x columns of the tile launch_gemm would pick for an M x N output
 bool gemm_segments_ok(int seg_k, int n_seg);  // seg_k a positive multiple of 128, 1 <= n_seg <= kMaxGemmSegments
 
@@ -81,9 +92,5 @@ hipError_t launch_rope(void* qkv, const float* cos_sin, int T, int S, int nh, in
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 // n bf16 values (a multiple of 8) -> fp32
 hipError_t launch_widen(void* dst_f32, const void* src_bf16, size_t n, hipStream_t s);
-// m = silu(gu[:, :F]) * gu[:, F:]
-hipError_t launch_swiglu_fwd(const void* gu, void* m, int T, int F, hipStream_t s);
-// dgu from dm and gu
-hipError_t launch_swiglu_bwd(const void* dm, const void* gu, void* dgu, int T, int F, hipStream_t s);
 
 }  // namespace ah

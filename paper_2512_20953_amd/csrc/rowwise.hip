@@ -1,7 +1,7 @@
 // Row-wise and element-wise kernels of the decoder layer: LayerNorm / RMSNorm
 // forward and backward (fused with the residual add and the column sums that
 // give the gains', offsets' and biases' gradients), column sums, rotary
-// embedding, SwiGLU.  All are bound by HBM bandwidth: every tensor is read and
+// embedding.  All are bound by HBM bandwidth: every tensor is read and
 // written once, 16 bytes per lane, statistics and sums in fp32.
 #include "common.h"
 #include "kernels.h"
@@ -421,42 +421,6 @@ __global__ __launch_bounds__(NT) void widen_kernel(const bf16* __restrict__ src,
   *(f32x4*)(dst + i * 8 + 4) = f32x4{bf2f(t[4]), bf2f(t[5]), bf2f(t[6]), bf2f(t[7])};
 }
 
-// ---------------------------------------------------------------- SwiGLU
-__global__ __launch_bounds__(NT) void swiglu_fwd_kernel(const bf16* __restrict__ gu, bf16* __restrict__ m, long n8, int F) {
-  const long idx = (long)blockIdx.x * NT + threadIdx.x;
-  if (idx >= n8) return;
-  const int per_row = F >> 3;
-  const long t = idx / per_row;
-  const int c = (idx % per_row) * 8;
-  bf16x8 g = *(const bf16x8*)(gu + t * 2 * F + c), u = *(const bf16x8*)(gu + t * 2 * F + F + c), o;
-#pragma unroll
-  for (int j = 0; j < 8; j++) {
-    const float x = bf2f(g[j]);
-    o[j] = f2bf(x / (1.f + __expf(-x)) * bf2f(u[j]));
-  }
-  *(bf16x8*)(m + t * F + c) = o;
-}
-
-__global__ __launch_bounds__(NT) void swiglu_bwd_kernel(const bf16* __restrict__ dm, const bf16* __restrict__ gu,
-                                                        bf16* __restrict__ dgu, long n8, int F) {
-  const long idx = (long)blockIdx.x * NT + threadIdx.x;
-  if (idx >= n8) return;
-  const int per_row = F >> 3;
-  const long t = idx / per_row;
-  const int c = (idx % per_row) * 8;
-  bf16x8 g = *(const bf16x8*)(gu + t * 2 * F + c), u = *(const bf16x8*)(gu + t * 2 * F + F + c);
-  bf16x8 d = *(const bf16x8*)(dm + t * F + c), og, ou;
-#pragma unroll
-  for (int j = 0; j < 8; j++) {
-    const float x = bf2f(g[j]), dd = bf2f(d[j]);
-    const float s = 1.f / (1.f + __expf(-x));
-    og[j] = f2bf(dd * bf2f(u[j]) * s * (1.f + x * (1.f - s)));
-    ou[j] = f2bf(dd * x * s);
-  }
-  *(bf16x8*)(dgu + t * 2 * F + c) = og;
-  *(bf16x8*)(dgu + t * 2 * F + F + c) = ou;
-}
-
 }  // namespace
 
 namespace {
@@ -587,19 +551,6 @@ hipError_t launch_widen(void* dst_f32, const void* src_bf16, size_t n, hipStream
   if (n % 8) return hipErrorInvalidValue;
   const size_t n8 = n / 8;
   hipLaunchKernelGGL(widen_kernel, dim3((unsigned)((n8 + NT - 1) / NT)), dim3(NT), 0, s, (const bf16*)src_bf16, (float*)dst_f32, n8);
-  return hipGetLastError();
-}
-
-hipError_t launch_swiglu_fwd(const void* gu, void* m, int T, int F, hipStream_t s) {
-  const long n8 = (long)T * F / 8;
-  hipLaunchKernelGGL(swiglu_fwd_kernel, dim3((unsigned)((n8 + NT - 1) / NT)), dim3(NT), 0, s, (const bf16*)gu, (bf16*)m, n8, F);
-  return hipGetLastError();
-}
-
-hipError_t launch_swiglu_bwd(const void* dm, const void* gu, void* dgu, int T, int F, hipStream_t s) {
-  const long n8 = (long)T * F / 8;
-  hipLaunchKernelGGL(swiglu_bwd_kernel, dim3((unsigned)((n8 + NT - 1) / NT)), dim3(NT), 0, s, (const bf16*)dm, (const bf16*)gu,
-                     (bf16*)dgu, n8, F);
   return hipGetLastError();
 }
 

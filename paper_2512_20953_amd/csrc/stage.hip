@@ -45,6 +45,7 @@ struct ah_stage {
   ah_stage_buffers_t bufs;
   int T, h, nh, d, hl, F, L;
   bool llama, causal, recompute, res32;
+  bool rope_in_gemm;  // the QKV product's tiles hold whole heads per wave: the rotary embedding runs in its epilogue
   float eps, rope_base;
   ParamEntry ptab[AH_P_COUNT];
   uint64_t layer_elems;
@@ -134,6 +135,10 @@ void plan(ah_stage* s, const ah_stage_config_t* c) {
     // tuning and test aid: the choice given outright, bit i = matrix i (second MLP, first MLP, out-projection, QKV)
     if (const char* m = getenv("AH_DEFER_MATRICES"))
       for (int i = 0; i < 4; i++) s->defer_matrix[i] = (atoi(m) >> i) & 1;
+  }
+  {
+    const int wc = gemm_min_wave_cols(s->T, 3 * s->hl, GEMM_NN);
+    s->rope_in_gemm = s->llama && wc > 0 && wc % s->d == 0 && !getenv("AH_ROPE_KERNEL");  // the variable: tuning aid
   }
   s->eps = c->norm_eps > 0 ? c->norm_eps : (s->llama ? 1e-6f : 1e-5f);
   s->rope_base = c->rope_base > 0 ? c->rope_base : 10000.f;
@@ -245,12 +250,12 @@ __global__ void fill_pattern_kernel(__bf16* p, size_t n, uint32_t seed) {
 enum Site {
   SITE_QKV_FWD, SITE_WO_FWD, SITE_FC1_FWD, SITE_FC2_FWD, SITE_FC2_WGRAD, SITE_FC2_DGRAD, SITE_FC1_WGRAD, SITE_FC1_DGRAD,
   SITE_WO_WGRAD, SITE_WO_DGRAD, SITE_QKV_WGRAD, SITE_QKV_DGRAD, SITE_ATTN_FWD, SITE_ATTN_BWD, SITE_NORM_FWD, SITE_NORM_BWD,
-  SITE_COLSUM, SITE_ROPE, SITE_SWIGLU_FWD, SITE_SWIGLU_BWD, SITE_COUNT
+  SITE_COLSUM, SITE_ROPE, SITE_COUNT
 };
 const char* const kSiteNames[SITE_COUNT] = {
   "gemm_nn.qkv_fwd", "gemm_nn.wo_fwd", "gemm_nn.fc1_fwd", "gemm_nn.fc2_fwd", "gemm_tn.fc2_wgrad", "gemm_nt.fc2_dgrad",
   "gemm_tn.fc1_wgrad", "gemm_nt.fc1_dgrad", "gemm_tn.wo_wgrad", "gemm_nt.wo_dgrad", "gemm_tn.qkv_wgrad", "gemm_nt.qkv_dgrad",
-  "attention_fwd", "attention_bwd", "norm_fwd", "norm_bwd", "colsum", "rope", "swiglu_fwd", "swiglu_bwd"};
+  "attention_fwd", "attention_bwd", "norm_fwd", "norm_bwd", "colsum", "rope"};
 
 // brackets the launches issued while it lives with an event pair when tracing
 struct SiteTimer {
@@ -417,8 +422,18 @@ hipError_t layer_forward(ah_stage* s, int layer, const ActPtrs& a, void* y, bool
   const GemmEpilogue resid = r32 ? EPI_RESID_F32 : EPI_RESID;
   const GemmEpilogue resid_out = r32 ? (y_is_stage_output ? EPI_RESID_F32_OUT16 : EPI_RESID_F32) : EPI_RESID;
   TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_in, p.ln1_g, p.ln1_b, a.a, (float*)a.stats1, T, h, s->eps, st, r32));
-  TRY(gemm(s, SITE_QKV_FWD, GEMM_NN, EPI_BF16, a.a, h, p.wqkv, 3 * hl, a.qkv, 3 * hl, T, 3 * hl, h, p.bqkv, nullptr, 0, nullptr, 0, st));
-  if (s->llama) TIMED(SITE_ROPE, launch_rope(a.qkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, 1.f, st));
+  if (s->llama && s->rope_in_gemm) {
+    // rotary embedding on Q and K in the epilogue of their product, on the fp32 sums
+    GemmArgs g = {};
+    g.A = a.a; g.B = p.wqkv; g.C = a.qkv;
+    g.lda = h; g.ldb = 3 * hl; g.ldc = 3 * hl; g.M = T; g.N = 3 * hl; g.K = h;
+    g.rope_cs = (const float*)P(s->bufs.workspace, s->ws.rope); g.rope_S = S; g.rope_d = s->d; g.rope_cols = 2 * hl;
+    SiteTimer t(s, SITE_QKV_FWD, st);
+    TRY(launch_gemm(GEMM_NN, EPI_ROPE, g, st));
+  } else {
+    TRY(gemm(s, SITE_QKV_FWD, GEMM_NN, EPI_BF16, a.a, h, p.wqkv, 3 * hl, a.qkv, 3 * hl, T, 3 * hl, h, p.bqkv, nullptr, 0, nullptr, 0, st));
+    if (s->llama) TIMED(SITE_ROPE, launch_rope(a.qkv, (const float*)P(s->bufs.workspace, s->ws.rope), T, S, s->nh, s->d, 1.f, st));
+  }
   TIMED(SITE_ATTN_FWD, launch_attention_fwd(a.qkv, a.o, (float*)a.lse, B, S, s->nh, s->d, s->causal, st));
   TRY(gemm(s, SITE_WO_FWD, GEMM_NN, resid, a.o, hl, p.wo, h, a.x_mid, h, T, h, hl, p.bo, a.x_in, h, nullptr, 0, st));
   TIMED(SITE_NORM_FWD, launch_norm_fwd(s->llama, a.x_mid, p.ln2_g, p.ln2_b, a.c, (float*)a.stats2, T, h, s->eps, st, r32));
@@ -481,8 +496,14 @@ hipError_t layer_backward(ah_stage* s, int layer, const ActPtrs& a, const void* 
     TRY(stream_order(st, sd, ev[1]));
     if (vp.finish) ON_SIDE(SITE_COLSUM, launch_colsum_finish(part_b1, T / 64, F, p.g_b1, beta, sd));
   } else {
-    TRY(gemm(s, SITE_FC2_DGRAD, GEMM_NT, EPI_BF16, dy, h, p.w2, h, dsm, F, T, F, h, nullptr, nullptr, 0, nullptr, 0, st));  // dm
-    TIMED(SITE_SWIGLU_BWD, launch_swiglu_bwd(dsm, a.u, du, T, F, st));                                                       // d(gate|up)
+    // d(gate | up) straight from the product dm = dy Wd^T: the SwiGLU backward is the GEMM's epilogue
+    GemmArgs g = {};
+    g.A = dy; g.B = p.w2; g.C = du; g.aux = a.u;
+    g.lda = h; g.ldb = h; g.ldc = 2 * F; g.ld_aux = 2 * F; g.swiglu_F = F; g.M = T; g.N = F; g.K = h;
+    {
+      SiteTimer t(s, SITE_FC2_DGRAD, st);
+      TRY(launch_gemm(GEMM_NT, EPI_SWIGLU_BWD, g, st));
+    }
     TRY(stream_order(st, sd, ev[1]));
   }
   TRY(wgrad(s, SITE_FC1_WGRAD, layer, WG_FC1, wp, a.c, du, p.g_w1, h, Fu, st, sd));
@@ -920,8 +941,6 @@ extern "C" int ah_stage_trace_end(ah_stage_t* st, ah_trace_entry_t* out, int cap
   bytes[SITE_NORM_FWD] = 4 * T * h + 8 * T;
   bytes[SITE_NORM_BWD] = 8 * T * h + 8 * T;
   bytes[SITE_ROPE] = 2 * (2 * T * 2 * hl);
-  bytes[SITE_SWIGLU_FWD] = 2 * T * 3 * F;
-  bytes[SITE_SWIGLU_BWD] = 2 * T * 5 * F;
   int n = 0;
   for (int sidx = 0; sidx < SITE_COUNT && n < capacity; sidx++) {
     if (!launches[sidx]) continue;
