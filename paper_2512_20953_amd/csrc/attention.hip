@@ -15,10 +15,11 @@
 // global->LDS loads into a 4-slot ring; loads run 3 tiles ahead and are waited
 // for by count, with one block barrier per tile.
 //
-// Backward is two deterministic kernels (no atomics): one block per 128 keys
-// accumulates dK and dV over the query tiles at or after it, one block per 128
-// queries accumulates dQ over the key tiles at or before it (causal; without the
-// mask both walk every tile of the sequence).
+// Backward is two deterministic kernels (no atomics): one block per 128
+// queries accumulates dQ over the key tiles at or before it and leaves
+// delta = rowsum(dO * O) of its queries behind; one block per 128 keys then
+// accumulates dK and dV over the query tiles at or after it (causal; without
+// the mask both walk every tile of the sequence).
 #include "common.h"
 #include "kernels.h"
 #include <cstdlib>
@@ -426,30 +427,22 @@ __global__ __launch_bounds__(256, 2) void attn_fwd64_kernel(const bf16* __restri
   if (hf == 0) lse[((size_t)b * nh + head) * S + q] = (m + __log2f(l)) * LN2;
 }
 
-// =========================================================================== backward: delta = rowsum(dO * O)
+// =========================================================================== backward: dQ (one block per 128 queries)
+// delta_q = sum_c dO[q, c] O[q, c] for the lane's query: the lane holds half of the row of dO as MFMA fragments
+// (columns ks * 16 + hf * 8 ..), reads the same columns of O, and the two lanes of a query add their halves.
+// The dQ kernels compute it for their own queries and leave it in `delta` for the dK/dV kernel, which runs after them.
 template <int D>
-__global__ __launch_bounds__(256) void attn_delta_kernel(const bf16* __restrict__ o, const bf16* __restrict__ d_o,
-                                                         float* __restrict__ delta, int T, int S, int nh) {
-  constexpr int LPR = D / 8;  // lanes per (token, head)
-  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-  const long row = idx / LPR;  // token * nh + head
-  const int piece = idx % LPR;
+__device__ __forceinline__ float row_delta(const bf16x8 (&dof)[D / 16], const bf16* __restrict__ orow, int hf) {
   float s = 0.f;
-  if (row < (long)T * nh) {
-    bf16x8 a = *(const bf16x8*)(o + row * D + piece * 8), b = *(const bf16x8*)(d_o + row * D + piece * 8);
 #pragma unroll
-    for (int j = 0; j < 8; j++) s += bf2f(a[j]) * bf2f(b[j]);
-  }
+  for (int ks = 0; ks < D / 16; ks++) {
+    const bf16x8 ov = *(const bf16x8*)(orow + ks * 16 + hf * 8);
 #pragma unroll
-  for (int w = LPR / 2; w > 0; w >>= 1) s += __shfl_xor(s, w, 64);
-  if (piece == 0 && row < (long)T * nh) {
-    const long t = row / nh;
-    const int head = row % nh;
-    delta[((t / S) * nh + head) * S + (t % S)] = s;
+    for (int j = 0; j < 8; j++) s = __builtin_fmaf(bf2f(dof[ks][j]), bf2f(ov[j]), s);
   }
+  return s + __shfl_xor(s, 32, 64);
 }
 
-// =========================================================================== backward: dQ (one block per 128 queries)
 template <int D>
 struct DqState {
   bf16x8 qf[D / 16], dof[D / 16];
@@ -543,9 +536,10 @@ __device__ __forceinline__ void dq_step(const bf16* gK, const bf16* gV, const ui
 }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
-                                                      const float* __restrict__ lse, const float* __restrict__ delta,
-                                                      bf16* __restrict__ dqkv, int S, int nh, float sc2, float scale) {
+__global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
+                                                      const bf16* __restrict__ d_o, const float* __restrict__ lse,
+                                                      float* __restrict__ delta, bf16* __restrict__ dqkv, int S, int nh,
+                                                      float sc2, float scale) {
   constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, LPS = 2 * (D / 32);  // ring slot = K tile then V tile
   __shared__ __attribute__((aligned(1024))) char ring[NSLOT * STAGE];
   const int lane = threadIdx.x & 63, hf = lane >> 5;
@@ -572,7 +566,8 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(const bf16* __restrict_
 #pragma unroll
     for (int r = 0; r < 16; r++) st.acc[dt][r] = 0.f;
   st.lse2 = lse[((size_t)b * nh + head) * S + q] * LOG2E;
-  st.delta = delta[((size_t)b * nh + head) * S + q];
+  st.delta = row_delta<D>(st.dof, o + ((size_t)b * S + q) * (nh * D) + head * D, hf);
+  if (hf == 0) delta[((size_t)b * nh + head) * S + q] = st.delta;
 
   uint32_t off[D / 32];
 #pragma unroll
@@ -687,9 +682,10 @@ __device__ __forceinline__ void dq_half_tile(const char* __restrict__ cK, const 
 }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void attn_dq64_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
-                                                        const float* __restrict__ lse, const float* __restrict__ delta,
-                                                        bf16* __restrict__ dqkv, int S, int nh, float sc2, float scale) {
+__global__ __launch_bounds__(256, 2) void attn_dq64_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
+                                                        const bf16* __restrict__ d_o, const float* __restrict__ lse,
+                                                        float* __restrict__ delta, bf16* __restrict__ dqkv, int S, int nh,
+                                                        float sc2, float scale) {
   constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, ND = D / 32;
   __shared__ __attribute__((aligned(1024))) char ring[NSLOT * STAGE];
   static_assert(2 * ND * 16 * 64 * 4 <= NSLOT * STAGE, "the partial results of two waves fit in the ring");
@@ -719,7 +715,8 @@ __global__ __launch_bounds__(256, 2) void attn_dq64_kernel(const bf16* __restric
 #pragma unroll
     for (int r = 0; r < 16; r++) st.acc[dt][r] = 0.f;
   st.lse2 = lse[((size_t)b * nh + head) * S + q] * LOG2E;
-  st.delta = delta[((size_t)b * nh + head) * S + q];
+  st.delta = row_delta<D>(st.dof, o + ((size_t)b * S + q) * (nh * D) + head * D, hf);   // both key halves compute it, one writes
+  if (hf == 0 && kh == 0) delta[((size_t)b * nh + head) * S + q] = st.delta;
 
   uint32_t off[D / 32];
 #pragma unroll
@@ -1185,21 +1182,21 @@ hipError_t launch_attention_fwd(const void* qkv, void* o, float* lse, int B, int
   return hipGetLastError();
 }
 
+// dQ first: it leaves the row sums delta = rowsum(dO * O) of its queries behind for the dK/dV kernel
 template <int D, bool CAUSAL>
-static void launch_bwd_t(dim3 grid, dim3 dgrid, hipStream_t s, const void* qkv, const void* o, const float* lse, const void* d_o,
-                         void* dqkv, float* delta, int T, int S, int nh, float sc2, float scale) {
-  hipLaunchKernelGGL(attn_delta_kernel<D>, dgrid, dim3(256), 0, s, (const bf16*)o, (const bf16*)d_o, delta, T, S, nh);
+static void launch_bwd_t(dim3 grid, hipStream_t s, const void* qkv, const void* o, const float* lse, const void* d_o,
+                         void* dqkv, float* delta, int S, int nh, float sc2, float scale) {
+  if ((int)grid.x <= small_grid_blocks())  // at most one 128-query block per CU: 64-query blocks with the keys split between wave pairs
+    hipLaunchKernelGGL((attn_dq64_kernel<D, CAUSAL>), dim3(2 * grid.x), dim3(256), 0, s, (const bf16*)qkv, (const bf16*)o, (const bf16*)d_o, lse,
+                       delta, (bf16*)dqkv, S, nh, sc2, scale);
+  else
+    hipLaunchKernelGGL((attn_dq_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)o, (const bf16*)d_o, lse, delta,
+                       (bf16*)dqkv, S, nh, sc2, scale);
   if ((int)grid.x <= small_grid_blocks())  // at most one 128-key block per CU: 64-key blocks with the queries split between wave pairs
     hipLaunchKernelGGL((attn_dkv64_kernel<D, CAUSAL>), dim3(2 * grid.x), dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta,
                        (bf16*)dqkv, S, nh, sc2, scale);
   else
     hipLaunchKernelGGL((attn_dkv_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv,
-                       S, nh, sc2, scale);
-  if ((int)grid.x <= small_grid_blocks())  // at most one 128-query block per CU: 64-query blocks with the keys split between wave pairs
-    hipLaunchKernelGGL((attn_dq64_kernel<D, CAUSAL>), dim3(2 * grid.x), dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta,
-                       (bf16*)dqkv, S, nh, sc2, scale);
-  else
-    hipLaunchKernelGGL((attn_dq_kernel<D, CAUSAL>), grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)d_o, lse, delta, (bf16*)dqkv,
                        S, nh, sc2, scale);
 }
 
@@ -1207,16 +1204,13 @@ hipError_t launch_attention_bwd(const void* qkv, const void* o, const float* lse
                                 int B, int S, int nh, int d, bool causal, hipStream_t s) {
   if (!attn_shape_ok(B, S, nh, d)) return hipErrorInvalidValue;
   const float scale = 1.f / sqrtf((float)d), sc2 = LOG2E * scale;
-  const int T = B * S;
   const dim3 grid(B * nh * (S / 128));
-  const long nthreads = (long)T * nh * (d / 8);
-  const dim3 dgrid((unsigned)((nthreads + 255) / 256));
   if (d == 128) {
-    if (causal) launch_bwd_t<128, true>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
-    else launch_bwd_t<128, false>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
+    if (causal) launch_bwd_t<128, true>(grid, s, qkv, o, lse, d_o, dqkv, delta, S, nh, sc2, scale);
+    else launch_bwd_t<128, false>(grid, s, qkv, o, lse, d_o, dqkv, delta, S, nh, sc2, scale);
   } else {
-    if (causal) launch_bwd_t<64, true>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
-    else launch_bwd_t<64, false>(grid, dgrid, s, qkv, o, lse, d_o, dqkv, delta, T, S, nh, sc2, scale);
+    if (causal) launch_bwd_t<64, true>(grid, s, qkv, o, lse, d_o, dqkv, delta, S, nh, sc2, scale);
+    else launch_bwd_t<64, false>(grid, s, qkv, o, lse, d_o, dqkv, delta, S, nh, sc2, scale);
   }
   return hipGetLastError();
 }
