@@ -146,3 +146,42 @@ def test_deferred_weight_gradient_configuration_and_sizes():
     vec = 2 * 3 * 64 * h * 4 + (T // 64) * F * 4 + (T // 64) * 3 * hl * 4
     assert s4["workspace_bytes"] - s0["workspace_bytes"] == 4 * 3 * block + 3 * vec
     assert {k: v for k, v in s4.items() if k != "workspace_bytes"} == {k: v for k, v in s0.items() if k != "workspace_bytes"}
+
+
+def test_layer_input_tap_points_into_the_slot():
+    """ah_stage_layer_input is pointer arithmetic over the caller's activation buffer: layer l of slot s sits at
+    s * (bytes per slot) + l * (bytes per layer and slot), also when only layer inputs are kept (recompute) and when
+    the residual stream is fp32; bad slots and layers are refused."""
+    from paper_2512_20953_amd.binding import _Buffers, lib
+    for kw in (dict(), dict(recompute=1), dict(res32=1), dict(recompute=1, res32=1)):
+        c = _cfg("tiny", n_layers=3, max_in_flight=2, **kw)
+        sz = query_sizes(c)
+        base = 1 << 20
+        h = ctypes.c_void_p()
+        assert lib.ah_stage_create(ctypes.byref(c), ctypes.byref(_Buffers(256, 512, base, 1024)), ctypes.byref(h)) == 0
+        p = ctypes.c_void_p()
+        for slot in (0, 1):
+            for layer in (0, 1, 2):
+                assert lib.ah_stage_layer_input(h, slot, layer, ctypes.byref(p)) == 0
+                assert p.value == base + slot * sz["activation_bytes_per_slot"] + layer * sz["activation_bytes_per_layer_per_slot"]
+        assert lib.ah_stage_layer_input(h, 2, 0, ctypes.byref(p)) == 1
+        assert lib.ah_stage_layer_input(h, 0, 3, ctypes.byref(p)) == 1
+        assert lib.ah_stage_layer_input(h, 0, 0, None) == 1
+        assert lib.ah_stage_destroy(h) == 0
+
+
+def test_residual_fp32_flag_is_validated():
+    with pytest.raises(P.AhError) as e:
+        query_sizes(_cfg("tiny", res32=2))
+    assert e.value.status == 1
+
+
+def test_new_single_kernel_entry_points_refuse_bad_arguments_without_touching_the_device():
+    from paper_2512_20953_amd.binding import lib
+    assert lib.ah_gemm_nn_swiglu(1, 1, 1, 1, 128, 100, 128, None) == 5       # F not a multiple of 128
+    assert lib.ah_gemm_nn_swiglu(1, 1, 1, 1, 128, 0, 128, None) == 5
+    assert lib.ah_gemm_nn_swiglu(1, None, 1, 1, 128, 128, 128, None) == 1
+    assert lib.ah_attention_bwd_static(1, 1, 1, 1, None, 1, 128, 1, 64, 1, None) == 1
+    assert lib.ah_attention_bwd_static(1, 1, 1, 1, 1, 1, 100, 1, 64, 1, None) == 5
+    assert lib.ah_attention_bwd_static(1, 1, 1, 1, 1, 4, 2048, 64, 64, 1, None) == 1     # 524288 rows: beyond the fixed scratch
+    assert b"exceeds" in lib.ah_last_error()
