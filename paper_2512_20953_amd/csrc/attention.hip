@@ -481,7 +481,7 @@ __device__ __forceinline__ void dq_tile(const char* __restrict__ cK, const char*
     if (AHEAD) AH_SCHED_FENCE();
     f32x16 s, dp;
 #pragma unroll
-    for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+    for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = -st.delta; }   // the product dO V^T lands on -delta: dP - delta for free
     bf16x8 kt[2][ND];
 #pragma unroll
     for (int ks = 0; ks < NK; ks++) {
@@ -501,10 +501,7 @@ __device__ __forceinline__ void dq_tile(const char* __restrict__ cK, const char*
     }
     const float nl = -st.lse2;
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      s[r] = fexp2(__builtin_fmaf(s[r], sc2, nl));
-      dp[r] -= st.delta;
-    }
+    for (int r = 0; r < 16; r++) s[r] = fexp2(__builtin_fmaf(s[r], sc2, nl));
     if (diag) {  // wave-uniform
 #pragma unroll
       for (int r = 0; r < 16; r++)
@@ -644,7 +641,7 @@ __device__ __forceinline__ void dq_half_tile(const char* __restrict__ cK, const 
   }
   f32x16 s, dp;
 #pragma unroll
-  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = -st.delta; }   // dP - delta for free
 #pragma unroll
   for (int ks = 0; ks < NK; ks++) {
     if (!AHEAD) {
@@ -664,10 +661,7 @@ __device__ __forceinline__ void dq_half_tile(const char* __restrict__ cK, const 
   }
   const float nl = -st.lse2;
 #pragma unroll
-  for (int r = 0; r < 16; r++) {
-    s[r] = fexp2(__builtin_fmaf(s[r], sc2, nl));
-    dp[r] -= st.delta;
-  }
+  for (int r = 0; r < 16; r++) s[r] = fexp2(__builtin_fmaf(s[r], sc2, nl));
   if (diag) {  // wave-uniform; element r is key kbase + 8*(r/4) + 4*hf + r%4
     const int lim = q - kbase - 4 * hf;
 #pragma unroll
@@ -797,12 +791,19 @@ __device__ __forceinline__ void dkv_tile(const char* __restrict__ cQ, const char
     fq[ks] = frag_rowmajor<D>(cQ, lane & 31, ks, hf);
     fo[ks] = frag_rowmajor<D>(cO, lane & 31, ks, hf);
   }
+  // delta of the lane's queries (q0 + t*32 + 8g + 4hf + i), read ahead with the fragments: the product dO V^T is
+  // accumulated onto -delta, which gives dP - delta without a subtraction per element
+  f32x4 dl[2][4];
+#pragma unroll
+  for (int t = 0; t < 2; t++)
+#pragma unroll
+    for (int g = 0; g < 4; g++) dl[t][g] = *(const f32x4*)(delta_tile + t * 32 + 8 * g + 4 * hf);
 #pragma unroll
   for (int t = 0; t < 2; t++) {
     AH_SCHED_FENCE();
     f32x16 s, dp;
 #pragma unroll
-    for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+    for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = -dl[t][r >> 2][r & 3]; }
     bf16x8 tq0[ND], to0[ND], tq1[ND], to1[ND];
 #pragma unroll
     for (int ks = 0; ks < NK; ks++) {
@@ -820,12 +821,10 @@ __device__ __forceinline__ void dkv_tile(const char* __restrict__ cQ, const char
     for (int g = 0; g < 4; g++) {
       const int ql = t * 32 + 8 * g + 4 * hf;
       const f32x4 l4 = *(const f32x4*)(lse_tile + ql);
-      const f32x4 d4 = *(const f32x4*)(delta_tile + ql);
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         const int r = 4 * g + i;
         s[r] = fexp2(__builtin_fmaf(s[r], sc2, -l4[i] * LOG2E));
-        dp[r] -= d4[i];
       }
     }
     if (diag) {  // wave-uniform: only tiles that straddle the diagonal pay for the mask
@@ -995,10 +994,13 @@ __device__ __forceinline__ void dkv_half_tile(const char* __restrict__ cQ, const
     fq[ks] = frag_rowmajor<D>(cQ, 32 * t + (lane & 31), ks, hf);
     fo[ks] = frag_rowmajor<D>(cO, 32 * t + (lane & 31), ks, hf);
   }
+  f32x4 dl[4];   // delta of the lane's queries: dO V^T is accumulated onto -delta
+#pragma unroll
+  for (int g = 0; g < 4; g++) dl[g] = *(const f32x4*)(delta_tile + t * 32 + 8 * g + 4 * hf);
   AH_SCHED_FENCE();
   f32x16 s, dp;
 #pragma unroll
-  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+  for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = -dl[r >> 2][r & 3]; }
   bf16x8 tq0[ND], to0[ND], tq1[ND], to1[ND];
 #pragma unroll
   for (int ks = 0; ks < NK; ks++) {
@@ -1016,12 +1018,10 @@ __device__ __forceinline__ void dkv_half_tile(const char* __restrict__ cQ, const
   for (int g = 0; g < 4; g++) {
     const int ql = t * 32 + 8 * g + 4 * hf;
     const f32x4 l4 = *(const f32x4*)(lse_tile + ql);
-    const f32x4 d4 = *(const f32x4*)(delta_tile + ql);
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       const int r = 4 * g + i;
       s[r] = fexp2(__builtin_fmaf(s[r], sc2, -l4[i] * LOG2E));
-      dp[r] -= d4[i];
     }
   }
   if (diag) {  // wave-uniform
