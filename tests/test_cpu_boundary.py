@@ -185,3 +185,12 @@ def test_new_single_kernel_entry_points_refuse_bad_arguments_without_touching_th
     assert lib.ah_attention_bwd_static(1, 1, 1, 1, 1, 1, 100, 1, 64, 1, None) == 5
     assert lib.ah_attention_bwd_static(1, 1, 1, 1, 1, 4, 2048, 64, 64, 1, None) == 1     # 524288 rows: beyond the fixed scratch
     assert b"exceeds" in lib.ah_last_error()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's stage: any other --gpus exits with a message, before anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""

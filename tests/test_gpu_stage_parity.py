@@ -242,8 +242,9 @@ def test_state_errors():
     torch.cuda.synchronize()
 
 
-def test_profile_reports_layers_and_bytes():
-    w = dict(SI.WORKLOADS["tiny"], n_layers=3)
+@pytest.mark.parametrize("name", ["tiny", "llama_res32_recompute"])
+def test_profile_reports_layers_and_bytes(name):
+    w = dict(SI.WORKLOADS[name] if name in SI.WORKLOADS else REDUCED[name], n_layers=3)
     gcfg, _ = U.make_cfgs(w, max_in_flight=2)
     st = P.Stage(gcfg)
     st.params.normal_(0, 0.02)
