@@ -168,11 +168,12 @@ def test_one_full_size_layer_of_each_workload(name, threaded_oracle):
 
 
 def _keep(name, rep, n_mb, w, seconds):
-    """The error figures of a full-depth case, kept beside the run's other results when that folder exists (never read back)."""
+    """The error figures of a full-depth case as a JSON file in the directory AH_TEST_REPORT_DIR names, if it names one
+    (written for whoever runs the tests; never read back)."""
     import json
     import os
-    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(out):
+    out = os.environ.get("AH_TEST_REPORT_DIR")
+    if out and os.path.isdir(out):
         with open(os.path.join(out, "full_depth_%s.json" % name), "w") as f:
             json.dump(dict(rep, workload=name, micro_batches=n_mb, layers=w["n_layers"], seconds=seconds), f)
 
