@@ -82,7 +82,7 @@ def main():
     ap.add_argument("--no-ungrouped", action="store_true", help="skip the comparison run with wgrad_group 1")
     ap.add_argument("--overlap", type=int, default=0,
                     help="1: forward of micro-batch m+1 is enqueued on a second stream beside backward of micro-batch m (they are "
-                         "independent; needs wgrad_group slots >= 2)")
+                         "independent; the stage is then created with at least two activation slots)")
     ap.add_argument("--no-side-stream", action="store_true",
                     help="keep all of backward on one stream, as the per-site trace does: kernel durations in a profile are then "
                          "those of kernels that own the chip (the timed figure is ~1 %% lower)")
@@ -104,9 +104,13 @@ def main():
     torch.manual_seed(SI.BASE_SEED)
     dev = torch.device("cuda:0")
     G = args.wgrad_group if args.wgrad_group > 0 else (1 if w["recompute"] else min(w["n_mb"], 16))
+    # forward of micro-batch m + 1 beside backward of micro-batch m: both need a slot, and with recomputation both would use
+    # the stage's one per-layer workspace, so that mode stays serial
+    overlap = bool(args.overlap) and w["n_mb"] >= 2 and not w["recompute"]
+    slots = max(G, 2) if overlap else G
     cfg = P.StageConfig.make(arch=w["arch"], n_layers=w["n_layers"], hidden=w["hidden"], n_heads=w["n_heads"],
                              head_dim=w["head_dim"], ffn=w["ffn"], tp=w["tp"], seq=w["seq"], mb=w["mb"], n_mb=w["n_mb"],
-                             max_in_flight=G, recompute=w["recompute"], wgrad_group=G, residual_fp32=w.get("res32", 0))
+                             max_in_flight=slots, recompute=w["recompute"], wgrad_group=G, residual_fp32=w.get("res32", 0))
     st = P.Stage(cfg, device=dev)
     # synthetic weights of the stated distribution, generated on the device: N(0, 0.02), gains 1, biases 0
     st.params.normal_(0.0, 0.02)
@@ -122,10 +126,10 @@ def main():
     y, dx = torch.empty_like(xs[0]), torch.empty_like(xs[0])
     stream = torch.cuda.current_stream()
 
-    overlap = bool(args.overlap) and G >= 2
     if overlap:
         fstream = torch.cuda.Stream()
         fdone = [torch.cuda.Event() for _ in range(K)]
+        bdone = [torch.cuda.Event() for _ in range(K)]
         ys2 = [torch.empty_like(xs[0]) for _ in range(2)]
         step_end = torch.cuda.Event()
 
@@ -133,20 +137,34 @@ def main():
         st.zero_grads(stream)
         if not overlap:
             for m in range(K):
-                st.forward(m % G, xs[m], y, stream)
-                st.backward(m % G, dys[m], dx, stream)
+                st.forward(m % slots, xs[m], y, stream)
+                st.backward(m % slots, dys[m], dx, stream)
         else:
-            # the forward passes run ahead on their own stream: F(m+1) beside B(m); B(m) waits for F(m)
+            # the forward passes run ahead on their own stream: F(m+1) beside B(m); B(m) waits for F(m).  A slot is free
+            # again once its previous micro-batch has had its backward (wgrad_group 1) or that micro-batch's group has been
+            # taken (the backward that closes the group): F waits for that backward, and is enqueued after it if need be.
             step_end.record(stream)
             fstream.wait_event(step_end)          # the slots were freed by the previous step's work on `stream`
-            st.forward(0, xs[0], ys2[0], fstream)
-            fdone[0].record(fstream)
+
+            def frees_slot_of(j):                 # the backward after which micro-batch j's slot is free again
+                return j if G == 1 else min((j // G) * G + G - 1, K - 1)
+
+            def forward(j):
+                if j - slots >= 0:
+                    fstream.wait_event(bdone[frees_slot_of(j - slots)])
+                st.forward(j % slots, xs[j], ys2[j % 2], fstream)
+                fdone[j].record(fstream)
+
+            forward(0)
             for m in range(K):
-                if m + 1 < K:
-                    st.forward((m + 1) % G, xs[m + 1], ys2[(m + 1) % 2], fstream)
-                    fdone[m + 1].record(fstream)
+                ahead = m + 1 < K and (m + 1 - slots < 0 or frees_slot_of(m + 1 - slots) < m)
+                if ahead:
+                    forward(m + 1)
                 stream.wait_event(fdone[m])
-                st.backward(m % G, dys[m], dx, stream)
+                st.backward(m % slots, dys[m], dx, stream)
+                bdone[m].record(stream)
+                if m + 1 < K and not ahead:
+                    forward(m + 1)
         st.flush_grads(stream)   # an incomplete last group (K not a multiple of G); otherwise nothing is pending
 
     for _ in range(args.warmup):

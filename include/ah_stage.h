@@ -157,7 +157,13 @@ int ah_stage_param_layout(const ah_stage_t* st, int layer, int which, uint64_t* 
 
 /* Forward of all layers for one micro-batch (the forward half of t_i^j).
  *   x : device, bf16 [B*S, hidden], read only.   y : device, bf16 [B*S, hidden], written.
- *   slot in [0, max_in_flight) must be empty; it becomes busy until its backward. */
+ *   slot in [0, max_in_flight) must be empty; it becomes busy until its backward.
+ * Micro-batches are independent until their gradients meet (Section III-A), so with recompute = 0 the forward of one
+ * slot may be enqueued on another stream than, and run beside, the backward of a different slot: forward writes only
+ * its slot and `y`.  The caller orders the two streams where they meet: a slot's backward after its forward, a slot's
+ * next forward after the backward that freed it.  With recompute = 1 forward and backward share the stage's one
+ * per-layer workspace and must be ordered against each other like calls on one stream.  The calls themselves are
+ * made from one host thread at a time. */
 int ah_stage_forward(ah_stage_t* st, int slot, const void* x, void* y, void* hip_stream);
 
 /* Backward of all layers for the micro-batch held in `slot` (the backward half

@@ -330,6 +330,60 @@ def test_second_stream_changes_no_bit(name, monkeypatch):
         assert torch.equal(g, outs[0][1])
 
 
+@pytest.mark.parametrize("name,group", [("gpt_d128_tp2", 0), ("gpt_d128_tp2", 2), ("llama_res32", 0)])
+def test_forward_beside_backward_changes_no_bit(name, group):
+    """Micro-batches are independent until their gradients meet (Section III-A): without recompute the forward of
+    micro-batch m + 1 may run on a second stream beside the backward of micro-batch m.  Outputs, input gradients and
+    the accumulated gradients must equal those of the serial order F0 B0 F1 B1 ... bit for bit.  Two slots; with
+    wgrad_group 2 a slot is free again only after the backward that closes its group, so that forward follows it."""
+    w = REDUCED[name]
+    K = 5
+    gcfg, _ = U.make_cfgs(w, max_in_flight=2, recompute=0, wgrad_group=group)
+    params, xs, dys = _inputs(w, n_mb=K)
+    st = P.Stage(gcfg)
+    U.load_params(st, params)
+    ys, dxs = U.run_gpu(st, xs, dys)
+    g_serial = st.grads.clone()
+
+    G, slots = max(group, 1), 2
+    main, ahead_stream = torch.cuda.current_stream(), torch.cuda.Stream()
+    xd, dyd = [U.to_dev(x) for x in xs], [U.to_dev(d) for d in dys]
+    yd, dxd = [torch.empty_like(x) for x in xd], [torch.empty_like(x) for x in xd]
+    fdone = [torch.cuda.Event() for _ in range(K)]
+    bdone = [torch.cuda.Event() for _ in range(K)]
+
+    def frees_slot_of(j):
+        return j if G == 1 else min((j // G) * G + G - 1, K - 1)
+
+    def forward(j):
+        if j - slots >= 0:
+            ahead_stream.wait_event(bdone[frees_slot_of(j - slots)])
+        st.forward(j % slots, xd[j], yd[j], ahead_stream)
+        fdone[j].record(ahead_stream)
+
+    for rep in range(2):
+        torch.cuda.synchronize()
+        st.grads.fill_(float("nan"))      # the first backward after zero_grads overwrites
+        st.zero_grads()
+        ahead_stream.wait_stream(main)
+        forward(0)
+        for m in range(K):
+            early = m + 1 < K and (m + 1 - slots < 0 or frees_slot_of(m + 1 - slots) < m)
+            if early:
+                forward(m + 1)
+            main.wait_event(fdone[m])
+            st.backward(m % slots, dyd[m], dxd[m], main)
+            bdone[m].record(main)
+            if m + 1 < K and not early:
+                forward(m + 1)
+        st.flush_grads()
+        torch.cuda.synchronize()
+        for m in range(K):
+            assert np.array_equal(U.to_np(yd[m]), ys[m]), (rep, m)
+            assert np.array_equal(U.to_np(dxd[m]), dxs[m]), (rep, m)
+        assert torch.equal(st.grads, g_serial), rep
+
+
 @pytest.mark.parametrize("group", [
     0,
     pytest.param(2, marks=pytest.mark.skip(
