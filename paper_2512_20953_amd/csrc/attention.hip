@@ -349,7 +349,7 @@ __device__ __forceinline__ void fwd_half_tile(const char* __restrict__ cK, const
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_fwd64_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o, float* __restrict__ lse,
                                                          int S, int nh, float sc2) {
-  constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, LPS = 2 * (D / 32), ND = D / 32;
+  constexpr int TILEB = 64 * 2 * D, STAGE = 2 * TILEB, ND = D / 32;
   __shared__ __attribute__((aligned(1024))) char ring[NSLOT * STAGE];
   static_assert(2 * (ND * 16 + 2) * 64 * 4 <= NSLOT * STAGE, "the partial results of two waves fit in the ring");
   const int lane = threadIdx.x & 63, hf = lane >> 5;

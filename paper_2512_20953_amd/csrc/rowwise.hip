@@ -23,17 +23,6 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return red[0] + red[1] + red[2] + red[3];
 }
 
-__device__ __forceinline__ void block_sum2(float& a, float& b, float* red) {
-  a = wave_sum(a);
-  b = wave_sum(b);
-  const int w = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) { red[w] = a; red[4 + w] = b; }
-  __syncthreads();
-  a = red[0] + red[1] + red[2] + red[3];
-  b = red[4] + red[5] + red[6] + red[7];
-}
-
 // Eight consecutive values of a tensor of the residual stream, which is bf16 or (residual_fp32) fp32.
 template <bool F32> struct XVec;
 template <> struct XVec<false> {
