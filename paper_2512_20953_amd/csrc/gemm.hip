@@ -290,7 +290,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < BN / 16 / NW; i++) offB[i] = loader_src_offset<BK, BN, BKS>(wave + NW * i, lane, g.ldb, GW, g.swiglu_F);
     // nk is a multiple of 4 (K is a multiple of 128).  Stage t lives in ring slot t % 4.
-    const int nk = g.K / BK, last = nk - 1;
+    const int nk = g.K / BK;
     // The k axis may be cut into pieces that live in different buffers (kernels.h): the outer loop runs over the
     // pieces, the inner one over the stages of a piece (a multiple of 4).  The stage fetched during local step t
     // is local stage t + 3; past the end of the piece that is a stage of the next piece, past the end of the last
